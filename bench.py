@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+A step is one forward + backward pass of the whole path (route, permute, grouped SwiGLU
+GEMMs, combine and their backward: every library call of paper_2508_02317_amd.layer) over
+one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Workloads are the five configurations of paper_2508_02317_amd.inputs.CONFIGS; the default
+is the 30B-A3B-class layer on one 8K-token micro-batch ("a3b_8k").
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 2048 MAC/clk x 2 x 2.4 GHz
+PEAK_FP32_TFLOPS = 157.3      # fp32 vector
+PEAK_HBM_GBS = 8000.0         # HBM3E
+PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (GPU model unstated), "
+                 "mixed precision -- context only")
+
+# HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this command
+# (summaries under profiles/), keyed by (workload, kernel); absent = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def kernel_work(cfg, P):
+    """Algorithmic work per launch of each kernel: ("mfma", flops) or ("hbm", bytes)."""
+    T, d, E, k, f = cfg.T, cfg.d, cfg.E, cfg.k, cfg.f
+    s = 2 if cfg.dtype == "bf16" else 4
+    dff = float(P) * d * f
+    mm = "mfma" if cfg.dtype == "bf16" else "alu"
+    pre = "ffn_" if cfg.dtype == "bf16" else "f32_"
+    work = {
+        pre + "gate_up": (mm, 4 * dff), pre + "down": (mm, 2 * dff), pre + "dact": (mm, 2 * dff),
+        pre + "dx": (mm, 4 * dff), "wgrad_down": (mm, 2 * dff), "wgrad_gate_up": (mm, 4 * dff),
+        "f32_wgrad": (mm, 2 * dff),
+        "route_topk": ("hbm", T * E * 4 + P * 8),
+        "route_bwd": ("hbm", T * E * 4 + P * 12),
+        "permute_gather": ("hbm", (T + P) * d * s + 2 * P * 4),
+        "combine_fwd": ("hbm", (P + T) * d * s + P * 8),
+        "combine_bwd": ("hbm", (T + 2 * P) * d * s + P * 12),
+    }
+    return work
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="a3b_8k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-save-gu", action="store_true", help="backward recomputes G and U")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1. "
+              "`value` is one GPU's throughput.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2508_02317_amd import libmoe as L
+    from paper_2508_02317_amd.inputs import CONFIGS, make_inputs, select_local_share
+    from paper_2508_02317_amd.layer import MoELayer
+
+    cfg = CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    t0 = time.time()
+    inp = make_inputs(cfg)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(tdt).contiguous()
+    wg, wu, wd = dev(inp["Wg"]), dev(inp["Wu"]), dev(inp["Wd"])
+    dy = dev(inp["dY"])
+    logits = torch.from_numpy(inp["logits"]).cuda()
+    prerouted = cfg.kind == "ep_share"
+    if prerouted:
+        # route the global problem with the library, cut this GPU's share by pure indexing
+        gidx, gw, _, _ = L.moe_route_topk(logits, cfg.k_global, cfg.renorm)
+        tok, lidx, lw = select_local_share(gidx.cpu().numpy(), gw.cpu().numpy(), cfg.E, cfg.T)
+        assert len(tok) == cfg.T, "global problem too small for the local share"
+        Xh = inp["X"][tok]
+        x = dev(Xh)
+        r_idx, r_w = torch.from_numpy(lidx).cuda(), torch.from_numpy(lw.astype(np.float32)).cuda()
+        counts_h = np.bincount(lidx[:, 0], minlength=cfg.E)
+        assert counts_h.max() > 5 * (cfg.T_global * cfg.k_global / cfg.E_global), "routing not skewed enough"
+    else:
+        Xh = inp["X"]
+        x = dev(Xh)
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, wg, wu, wd, renorm=cfg.renorm, prerouted=prerouted,
+                     save_gu=not args.no_save_gu)
+    P = layer.P
+    print("[bench] %s: inputs ready in %.1f s" % (cfg.name, time.time() - t0), file=sys.stderr, flush=True)
+
+    def step():
+        if prerouted:
+            layer.forward(x, topk_idx=r_idx, topk_w=r_w)
+            layer.backward(dy)
+        else:
+            layer.forward(x, logits=logits)
+            layer.backward(dy, logits=logits)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = cfg.T * args.steps / elapsed
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream, same K steps
+    L.moe_profile_enable(1)
+    torch.cuda.synchronize()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = L.moe_profile_report()
+    L.moe_profile_enable(0)
+
+    work = kernel_work(cfg, P)
+    kernels = {}
+    for name, (count, total_ms) in prof.items():
+        avg_ms = total_ms / count
+        entry = {"launches_per_step": count / args.steps, "avg_ms": round(avg_ms, 5)}
+        if name in work:
+            bound, amount = work[name]
+            if bound == "hbm":
+                entry.update(bound="hbm", achieved=round(amount / (avg_ms * 1e-3) / 1e9, 1), unit="GB/s", peak=PEAK_HBM_GBS)
+            else:
+                peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
+                entry.update(bound=bound, achieved=round(amount / (avg_ms * 1e-3) / 1e12, 2), unit="TFLOP/s", peak=peak)
+            entry["frac"] = round(entry["achieved"] / entry["peak"], 4)
+        kernels[name] = entry
+    dominant = max((n for n in kernels if "frac" in kernels[n]),
+                   key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
+    dk = kernels[dominant]
+    roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
+                "unit": dk["unit"], "frac": dk["frac"], "avg_ms": dk["avg_ms"],
+                "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant))}
+    gemm_names = [n for n in kernels if kernels[n].get("bound") in ("mfma", "alu")]
+    gemm_ms = sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in gemm_names)
+    gemm_tflops = 18.0 * P * cfg.d * cfg.f / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    gemm_peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+
+    out = {
+        "metric": "MoE layer fwd+bwd tokens/sec on 1 MI355X; grouped-GEMM % of bf16 MFMA peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "k": cfg.k, "f": cfg.f, "P": P,
+                   "renorm": cfg.renorm, "save_gu": not args.no_save_gu,
+                   "unit_note": "routed rows/s" if prerouted else "tokens/s"},
+        "roofline": roofline,
+        "grouped_gemm": {"tflops": round(gemm_tflops, 2), "frac_of_peak": round(gemm_tflops / gemm_peak, 4),
+                         "peak": gemm_peak, "ms_per_step": round(gemm_ms, 4)},
+        "kernels": kernels,
+        "context": PAPER_CONTEXT,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, Xh, layer, prerouted,
+                                           (lidx, lw) if prerouted else None)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg, inp, Xh, layer, prerouted, routing):
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample: the
+    first Ts tokens of the same workload (tokens are independent in the forward, so its Y
+    and dX rows are also a parity check of the GPU result)."""
+    import numpy as np
+    from oracle import moe_oracle as O
+    flops_per_token = 18.0 * cfg.d * cfg.f * cfg.k
+    Ts = int(min(cfg.T, max(64, 1.0e12 // flops_per_token)))      # about 1 TFLOP of fp64 work
+    X, dY = Xh[:Ts], inp["dY"][:Ts]
+    t0 = time.perf_counter()
+    if prerouted:
+        fwd = O.moe_layer_fwd(X, None, inp["Wg"], inp["Wu"], inp["Wd"], 1,
+                              routing=(routing[0][:Ts], routing[1][:Ts].astype(np.float32)))
+        bwd = O.moe_layer_bwd(fwd, dY, None, inp["Wg"], inp["Wu"], inp["Wd"])
+    else:
+        z = inp["logits"][:Ts]
+        fwd = O.moe_layer_fwd(X, z, inp["Wg"], inp["Wu"], inp["Wd"], cfg.k, cfg.renorm)
+        bwd = O.moe_layer_bwd(fwd, dY, z, inp["Wg"], inp["Wu"], inp["Wd"], cfg.renorm)
+    dt = time.perf_counter() - t0
+    y = layer.y[:Ts].float().cpu().numpy().astype(np.float64)
+    dx = layer.dx[:Ts].float().cpu().numpy().astype(np.float64)
+    err_y = float(np.max(np.abs(y - fwd["Y"])) / np.max(np.abs(fwd["Y"])))
+    err_dx = float(np.max(np.abs(dx - bwd["dX"])) / np.max(np.abs(bwd["dX"])))
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    return {"value": round(Ts / dt, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "first %d of %d tokens, full fwd+bwd in numpy fp64 (%.1f s)" % (Ts, cfg.T, dt),
+            "host_cores_available": len(os.sched_getaffinity(0)),
+            "parity_on_sample": {"Y": err_y, "dX": err_dx}}
+
+
+if __name__ == "__main__":
+    main()

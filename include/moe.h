@@ -1,0 +1,176 @@
+/*
+ * libmoe -- C ABI of the MI355X (gfx950) mixture-of-experts hot path.
+ *
+ * One GPU's share of a dropless top-k routed SwiGLU MoE feed-forward layer, forward and
+ * backward.  The paper names this path only in prose: tokens are routed to a sparse
+ * subset of experts (Sec. 3.2.3), each expert is a SwiGLU block served by "MoE-specific
+ * operations" (Sec. 3.2.5, Efficient Kernels), and the expert weights are three stacked
+ * tensors gate_proj / up_proj / down_proj with the expert on dim 0 (App. B.6, the
+ * expert-parallel plan listing).  The arithmetic below is the standard definition of
+ * such a layer:
+ *
+ *     S(t)    = k experts with the largest logit z[t,:], ordered (logit desc, index asc)
+ *     w[t,j]  = softmax(z[t,:])[e_j], divided by the sum over the k selected if renorm
+ *     FFN_e x = W_down[e] ( silu(W_gate[e] x) * (W_up[e] x) ),  silu(g) = g / (1 + exp(-g))
+ *     Y[t]    = sum_j w[t,j] FFN_{e_j}(X[t])
+ *
+ * Conventions shared by every entry point
+ *   - Pointers are DEVICE pointers unless marked [host].  The caller owns all memory,
+ *     including workspaces; the library allocates nothing, frees nothing and keeps no
+ *     pointer after a call returns.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and return without synchronising.  No device-to-host copy happens inside.
+ *   - Matrices are dense row-major with 16-byte aligned base addresses.
+ *   - dtype selects the element type of activations and expert weights: MOE_F32 or
+ *     MOE_BF16 (bf16 operands, fp32 accumulation, one rounding to bf16 on output).
+ *     Router logits, combine weights and their gradients are always fp32; indices,
+ *     counts, offsets and maps are int32.  P = T * k routed rows must fit in int32.
+ *   - Weight layout: w_gate, w_up : [E, f, d];  w_down : [E, d, f]  (expert-major,
+ *     out-features x in-features); gradients use the layout and dtype of their weight.
+ *   - Every entry point validates its arguments on the host first; when it returns a
+ *     non-zero status nothing has been launched.  moe_last_error() gives the reason.
+ *   - Limits: 1 <= k <= 64, k <= E <= 1024; d and f multiples of 8; sizes > 0 except
+ *     that T (or P) may be 0, which is a no-op.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = 1, /* null / misaligned pointer, non-positive size, k > E            */
+  MOE_ERR_UNSUPPORTED = 2, /* dtype or shape outside the limits listed above                 */
+  MOE_ERR_WORKSPACE = 3,   /* workspace pointer null or smaller than *_workspace_bytes says  */
+  MOE_ERR_HIP = 4          /* a launch failed; see moe_last_error()                          */
+};
+
+enum { MOE_F32 = 0, MOE_BF16 = 1 };
+
+/* Library version, "major.minor.patch" ([host] static string). */
+const char* moe_version(void);
+
+/* Text of the last error on the calling thread ([host], owned by the library, valid until
+ * the next failing call on this thread; empty string if none). */
+const char* moe_last_error(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Routing (Sec. 3.2.3: tokens are routed to their assigned experts).
+ *
+ * For each token t: the k experts with the largest logits[t,:] (ties to the lower expert
+ * index; +0 and -0 compare equal; logits must be finite), in slot order (logit descending,
+ * index ascending); combine weights = softmax over all E experts, renormalised over the k
+ * selected when renorm != 0; counts[e] = number of (token, slot) pairs routed to e;
+ * offsets = exclusive prefix sum of counts, offsets[E] = T*k.
+ *
+ *   logits   [T,E] f32 in     topk_idx [T,k] i32 out    topk_w  [T,k] f32 out
+ *   counts   [E]   i32 out    offsets  [E+1] i32 out
+ *   ws / ws_bytes: scratch of at least moe_route_topk_workspace_bytes(T,E,k) bytes.
+ */
+size_t moe_route_topk_workspace_bytes(int T, int E, int k);
+int32_t moe_route_topk(const float* logits, int T, int E, int k, int renorm,
+                       int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Counts and offsets of an assignment that is already known (rows that an expert-parallel
+ * dispatch has delivered to this GPU, Sec. 3.2.3: one local expert id per row, k = 1):
+ * counts[e] = #{p : topk_idx[p] == e}, offsets = exclusive prefix sum, offsets[E] = n_pairs.
+ *   topk_idx [n_pairs] i32 in (values in [0,E)); counts [E], offsets [E+1] i32 out;
+ *   ws of at least moe_expert_offsets_workspace_bytes(n_pairs, E) bytes.
+ */
+size_t moe_expert_offsets_workspace_bytes(int n_pairs, int E);
+int32_t moe_expert_offsets(const int32_t* topk_idx, int n_pairs, int E, int32_t* counts,
+                           int32_t* offsets, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the combine weights with respect to the logits, selection held fixed.
+ *   renorm != 0:  dlogits[t,e_j] = w_j (dw_j - sum_m w_m dw_m), 0 for unselected experts
+ *   renorm == 0:  dlogits[t,e]   = p_e (1[e in S] dw_e - sum_{m in S} p_m dw_m), p = softmax(logits)
+ *   dw, topk_w [T,k] f32 in; topk_idx [T,k] i32 in; logits [T,E] f32 in (read only when
+ *   renorm == 0, may be NULL otherwise); dlogits [T,E] f32 out, every element written.
+ */
+int32_t moe_route_topk_bwd(const float* dw, const float* topk_w, const int32_t* topk_idx,
+                           const float* logits, int T, int E, int k, int renorm,
+                           float* dlogits, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Permutation into expert-contiguous rows (the local half of the token dispatch of
+ * Sec. 3.2.3).  Stable counting sort of the P = T*k pairs p = t*k+j by expert:
+ *   row_of_pair[p] = offsets[e_p] + #{p' < p : e_p' = e_p},  pair_of_row = its inverse,
+ *   xp[row_of_pair[t*k+j], :] = x[t, :]   (bit copy).
+ *   x [T,d] in; topk_idx [T,k] in; offsets [E+1] in (as written by moe_route_topk, or the
+ *   exclusive scan of the bincount of topk_idx for pre-routed rows with k = 1);
+ *   xp [P,d] out; row_of_pair, pair_of_row [P] i32 out.
+ */
+size_t moe_permute_workspace_bytes(int T, int E, int k);
+int32_t moe_permute(const void* x, int dtype, int T, int d, int E, int k,
+                    const int32_t* topk_idx, const int32_t* offsets,
+                    void* xp, int32_t* row_of_pair, int32_t* pair_of_row,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Grouped SwiGLU expert FFN (Sec. 3.2.5 SwiGLU; App. B.6 stacked expert weights).
+ * For each expert e and its rows r in [offsets[e], offsets[e+1]):
+ *   G = xp W_gate[e]^T,  U = xp W_up[e]^T,  act = silu(G) * U,  yp = act W_down[e]^T.
+ *   xp [P,d] in; offsets [E+1] in (offsets[E] == P); act [P,f] out; yp [P,d] out;
+ *   g_save, u_save [P,f] out, or both NULL when the caller will let the backward recompute.
+ */
+size_t moe_grouped_gemm_swiglu_fwd_workspace_bytes(int dtype, int P, int d, int f, int E);
+int32_t moe_grouped_gemm_swiglu_fwd(const void* xp, const void* w_gate, const void* w_up,
+                                    const void* w_down, int dtype, int P, int d, int f, int E,
+                                    const int32_t* offsets, void* g_save, void* u_save,
+                                    void* act, void* yp, void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the grouped FFN.  Per expert:
+ *   dA = dyp W_down[e];  dW_down[e] = dyp^T act;  dG = dA * U * silu'(G);  dU = dA * silu(G);
+ *   dW_gate[e] = dG^T xp;  dW_up[e] = dU^T xp;  dxp = dG W_gate[e] + dU W_up[e].
+ * All three weight gradients are overwritten (not accumulated); experts without rows get
+ * zeros.  g_save / u_save may both be NULL: G and U are then recomputed from xp (act is
+ * still required).  `have_saved` in the workspace query says which variant will be called.
+ */
+size_t moe_grouped_gemm_swiglu_bwd_workspace_bytes(int dtype, int P, int d, int f, int E, int have_saved);
+int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, const void* g_save,
+                                    const void* u_save, const void* act, const void* w_gate,
+                                    const void* w_up, const void* w_down, int dtype, int P, int d,
+                                    int f, int E, const int32_t* offsets, void* dxp, void* dw_gate,
+                                    void* dw_up, void* dw_down, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Weighted un-permute / combine (the return half of the dispatch of Sec. 3.2.3).
+ *   y[t,:] = sum_{j<k} topk_w[t,j] * yp[row_of_pair[t*k+j], :]   (fp32 sum, j ascending)
+ * topk_w == NULL means all weights 1: that is the backward of moe_permute
+ * (dx[t] = sum_j dxp[row_of_pair[t*k+j]]).
+ */
+int32_t moe_unpermute_combine_fwd(const void* yp, int dtype, int T, int d, int k,
+                                  const float* topk_w, const int32_t* row_of_pair,
+                                  void* y, void* stream);
+
+/* Backward of the combine:
+ *   dyp[row_of_pair[t*k+j], :] = topk_w[t,j] * dy[t,:];   dw[t,j] = <dy[t,:], yp[row,:]>.
+ *   dy [T,d], yp [P,d] in; dyp [P,d] out; dw [T,k] f32 out.
+ */
+int32_t moe_unpermute_combine_bwd(const void* dy, const void* yp, int dtype, int T, int d, int k,
+                                  const float* topk_w, const int32_t* row_of_pair,
+                                  void* dyp, float* dw, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Per-kernel timing for measurement harnesses (not part of the layer's arithmetic).
+ * moe_profile_enable(1): from now on every kernel the library launches is bracketed by a
+ * pair of HIP events recorded on the launch stream (the library creates the events it
+ * needs; this is the only place it allocates anything).  moe_profile_enable(0) stops it.
+ * Either call discards records not yet reported.
+ * moe_profile_report: waits for the recorded events, writes one line per kernel
+ * "name launches total_milliseconds\n" into buf ([host], cap bytes, NUL-terminated,
+ * truncated if too small), clears the records and returns the size needed.
+ */
+int32_t moe_profile_enable(int on);
+size_t moe_profile_report(char* buf, size_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

@@ -1,0 +1,159 @@
+// Host-side entry points of the grouped expert FFN plus the library's error reporting.
+// Argument validation happens here, before anything is launched.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+#include "moe_common.h"
+
+namespace moe {
+
+static thread_local char g_error[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int32_t check_launch(const char* what) {
+  hipError_t err = hipGetLastError();
+  if (err == hipSuccess) return MOE_OK;
+  return fail(MOE_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
+}
+
+// ---- per-kernel event timing -------------------------------------------------------------------
+namespace {
+struct ProfRecord { const char* name; hipEvent_t start, stop; };
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof_records;     // records in use
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;   // events ready for reuse
+}  // namespace
+
+ProfScope::ProfScope(const char* name, hipStream_t stream) : stream_(stream), slot_(-1) {
+  if (!g_prof_on) return;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  ProfRecord r{name, nullptr, nullptr};
+  if (!g_prof_pool.empty()) {
+    r.start = g_prof_pool.back().first;
+    r.stop = g_prof_pool.back().second;
+    g_prof_pool.pop_back();
+  } else if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
+    return;
+  }
+  (void)hipEventRecord(r.start, stream);
+  g_prof_records.push_back(r);
+  slot_ = static_cast<int>(g_prof_records.size()) - 1;
+}
+
+ProfScope::~ProfScope() {
+  if (slot_ < 0) return;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  (void)hipEventRecord(g_prof_records[slot_].stop, stream_);
+}
+
+static int32_t check_ffn_dims(const char* who, int dtype, int P, int d, int f, int E) {
+  MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, dtype);
+  MOE_REQUIRE(P >= 0 && d > 0 && f > 0 && E > 0, MOE_ERR_INVALID_ARG, "%s: need P >= 0, d, f, E > 0 (P=%d d=%d f=%d E=%d)", who, P, d, f, E);
+  MOE_REQUIRE(E <= kMaxExperts, MOE_ERR_UNSUPPORTED, "%s: E=%d above the built maximum %d", who, E, kMaxExperts);
+  MOE_REQUIRE(d % 8 == 0 && f % 8 == 0, MOE_ERR_UNSUPPORTED, "%s: d=%d and f=%d must be multiples of 8", who, d, f);
+  MOE_REQUIRE(static_cast<int64_t>(E) * d * f <= (int64_t{1} << 40), MOE_ERR_UNSUPPORTED, "%s: weights too large", who);
+  return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" const char* moe_version(void) { return "0.1.0"; }
+extern "C" const char* moe_last_error(void) { return g_error; }
+
+extern "C" int32_t moe_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  for (auto& r : g_prof_records) g_prof_pool.emplace_back(r.start, r.stop);
+  g_prof_records.clear();
+  g_prof_on = on != 0;
+  return MOE_OK;
+}
+
+extern "C" size_t moe_profile_report(char* buf, size_t cap) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  struct Agg { long count = 0; double ms = 0.0; };
+  std::map<std::string, Agg> agg;
+  std::vector<std::string> order;
+  for (auto& r : g_prof_records) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
+    if (!agg.count(r.name)) order.push_back(r.name);
+    Agg& a = agg[r.name];
+    a.count += 1;
+    a.ms += ms;
+  }
+  for (auto& r : g_prof_records) g_prof_pool.emplace_back(r.start, r.stop);
+  g_prof_records.clear();
+  std::string out;
+  char line[256];
+  for (auto& name : order) {
+    snprintf(line, sizeof(line), "%s %ld %.6f\n", name.c_str(), agg[name].count, agg[name].ms);
+    out += line;
+  }
+  if (buf && cap > 0) {
+    size_t n = out.size() < cap - 1 ? out.size() : cap - 1;
+    memcpy(buf, out.data(), n);
+    buf[n] = 0;
+  }
+  return out.size() + 1;
+}
+
+extern "C" size_t moe_grouped_gemm_swiglu_fwd_workspace_bytes(int dtype, int P, int d, int f, int E) {
+  if (P < 0 || d <= 0 || f <= 0 || E <= 0) return 0;
+  return dtype == MOE_BF16 ? ffn_fwd_ws_bytes_bf16(P, d, f, E) : ffn_fwd_ws_bytes_f32(P, d, f, E);
+}
+
+extern "C" size_t moe_grouped_gemm_swiglu_bwd_workspace_bytes(int dtype, int P, int d, int f, int E, int have_saved) {
+  if (P < 0 || d <= 0 || f <= 0 || E <= 0) return 0;
+  return dtype == MOE_BF16 ? ffn_bwd_ws_bytes_bf16(P, d, f, E, have_saved) : ffn_bwd_ws_bytes_f32(P, d, f, E, have_saved);
+}
+
+extern "C" int32_t moe_grouped_gemm_swiglu_fwd(const void* xp, const void* w_gate, const void* w_up,
+                                               const void* w_down, int dtype, int P, int d, int f, int E,
+                                               const int32_t* offsets, void* g_save, void* u_save,
+                                               void* act, void* yp, void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_ffn_dims("ffn_fwd", dtype, P, d, f, E)) return rc;
+  MOE_REQUIRE((g_save == nullptr) == (u_save == nullptr), MOE_ERR_INVALID_ARG, "ffn_fwd: g_save and u_save must both be given or both be null");
+  if (P == 0) return MOE_OK;
+  MOE_REQUIRE(xp && w_gate && w_up && w_down && offsets && act && yp, MOE_ERR_INVALID_ARG, "ffn_fwd: null pointer");
+  MOE_REQUIRE(aligned16(xp) && aligned16(w_gate) && aligned16(w_up) && aligned16(w_down) && aligned16(act) && aligned16(yp) &&
+              aligned16(g_save) && aligned16(u_save), MOE_ERR_INVALID_ARG, "ffn_fwd: tensors must be 16-byte aligned");
+  const size_t need = moe_grouped_gemm_swiglu_fwd_workspace_bytes(dtype, P, d, f, E);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_fwd: workspace null, misaligned or smaller than %zu bytes", need);
+  FfnFwdArgs a{xp, w_gate, w_up, w_down, P, d, f, E, offsets, g_save, u_save, act, yp, ws, static_cast<hipStream_t>(stream)};
+  if (dtype == MOE_BF16) ffn_fwd_bf16(a); else ffn_fwd_f32(a);
+  return check_launch("moe_grouped_gemm_swiglu_fwd");
+}
+
+extern "C" int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, const void* g_save,
+                                               const void* u_save, const void* act, const void* w_gate,
+                                               const void* w_up, const void* w_down, int dtype, int P, int d,
+                                               int f, int E, const int32_t* offsets, void* dxp, void* dw_gate,
+                                               void* dw_up, void* dw_down, void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_ffn_dims("ffn_bwd", dtype, P, d, f, E)) return rc;
+  MOE_REQUIRE((g_save == nullptr) == (u_save == nullptr), MOE_ERR_INVALID_ARG, "ffn_bwd: g_save and u_save must both be given or both be null");
+  MOE_REQUIRE(offsets && dw_gate && dw_up && dw_down, MOE_ERR_INVALID_ARG, "ffn_bwd: null offsets or weight-gradient pointer");
+  MOE_REQUIRE(P == 0 || (dyp && xp && act && w_gate && w_up && w_down && dxp), MOE_ERR_INVALID_ARG, "ffn_bwd: null pointer");
+  MOE_REQUIRE(aligned16(dyp) && aligned16(xp) && aligned16(act) && aligned16(g_save) && aligned16(u_save) && aligned16(w_gate) &&
+              aligned16(w_up) && aligned16(w_down) && aligned16(dxp) && aligned16(dw_gate) && aligned16(dw_up) && aligned16(dw_down),
+              MOE_ERR_INVALID_ARG, "ffn_bwd: tensors must be 16-byte aligned");
+  const size_t need = moe_grouped_gemm_swiglu_bwd_workspace_bytes(dtype, P, d, f, E, g_save != nullptr);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_bwd: workspace null, misaligned or smaller than %zu bytes", need);
+  FfnBwdArgs a{dyp, xp, g_save, u_save, act, w_gate, w_up, w_down, P, d, f, E, offsets, dxp, dw_gate, dw_up, dw_down, ws,
+               static_cast<hipStream_t>(stream)};
+  if (dtype == MOE_BF16) ffn_bwd_bf16(a); else ffn_bwd_f32(a);
+  return check_launch("moe_grouped_gemm_swiglu_bwd");
+}

@@ -1,0 +1,172 @@
+// fp32 variant of the grouped SwiGLU expert FFN (Sec. 3.2.5; stacked weights of App. B.6).
+//
+// This element type exists for the small full-precision parity configuration; its sizes
+// are launch-latency bound, so the kernels are written for exactness and clarity: one
+// thread per output element, a sequential fp32 FMA chain over the reduction index, no
+// tiling.  The bf16 MFMA path lives in gemm_bf16.hip.
+#include "moe_common.h"
+
+namespace moe {
+
+constexpr int kF32Threads = 256;
+
+// expert whose row segment [offsets[e], offsets[e+1]) contains row r
+__device__ __forceinline__ int expert_of_row(const int32_t* __restrict__ offsets, int E, int r) {
+  int lo = 0, hi = E;          // invariant: offsets[lo] <= r < offsets[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (offsets[mid] <= r) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// G = xp Wg^T, U = xp Wu^T, act = silu(G) * U          one thread per (row, n)
+__global__ __launch_bounds__(kF32Threads) void f32_gate_up_kernel(
+    const float* __restrict__ xp, const float* __restrict__ wg, const float* __restrict__ wu,
+    int P, int d, int f, int E, const int32_t* __restrict__ offsets,
+    float* __restrict__ G, float* __restrict__ U, float* __restrict__ act) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
+  if (i >= static_cast<size_t>(P) * f) return;
+  const int r = static_cast<int>(i / f), n = static_cast<int>(i % f);
+  const int e = expert_of_row(offsets, E, r);
+  const float* x = xp + static_cast<size_t>(r) * d;
+  const float* g_row = wg + (static_cast<size_t>(e) * f + n) * d;
+  const float* u_row = wu + (static_cast<size_t>(e) * f + n) * d;
+  float g = 0.0f, u = 0.0f;
+  for (int c = 0; c < d; ++c) { g = fmaf(x[c], g_row[c], g); u = fmaf(x[c], u_row[c], u); }
+  if (G) G[i] = g;
+  if (U) U[i] = u;
+  if (act) act[i] = g * sigmoid_acc(g) * u;
+}
+
+// yp = act Wd^T                                         one thread per (row, c)
+__global__ __launch_bounds__(kF32Threads) void f32_down_kernel(
+    const float* __restrict__ act, const float* __restrict__ wd, int P, int d, int f, int E,
+    const int32_t* __restrict__ offsets, float* __restrict__ yp) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
+  if (i >= static_cast<size_t>(P) * d) return;
+  const int r = static_cast<int>(i / d), c = static_cast<int>(i % d);
+  const int e = expert_of_row(offsets, E, r);
+  const float* a = act + static_cast<size_t>(r) * f;
+  const float* w = wd + (static_cast<size_t>(e) * d + c) * f;
+  float s = 0.0f;
+  for (int n = 0; n < f; ++n) s = fmaf(a[n], w[n], s);
+  yp[i] = s;
+}
+
+// dA = dyp Wd;  dG = dA * U * silu'(G);  dU = dA * silu(G)      one thread per (row, n)
+__global__ __launch_bounds__(kF32Threads) void f32_dact_kernel(
+    const float* __restrict__ dyp, const float* __restrict__ wd, const float* __restrict__ G,
+    const float* __restrict__ U, int P, int d, int f, int E, const int32_t* __restrict__ offsets,
+    float* __restrict__ dG, float* __restrict__ dU) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
+  if (i >= static_cast<size_t>(P) * f) return;
+  const int r = static_cast<int>(i / f), n = static_cast<int>(i % f);
+  const int e = expert_of_row(offsets, E, r);
+  const float* dy = dyp + static_cast<size_t>(r) * d;
+  const float* w = wd + static_cast<size_t>(e) * d * f + n;
+  float da = 0.0f;
+  for (int c = 0; c < d; ++c) da = fmaf(dy[c], w[static_cast<size_t>(c) * f], da);
+  const float g = G[i], u = U[i];
+  const float s = sigmoid_acc(g);
+  dG[i] = da * u * (s * (1.0f + g * (1.0f - s)));
+  dU[i] = da * (g * s);
+}
+
+// dxp = dG Wg + dU Wu                                    one thread per (row, c)
+__global__ __launch_bounds__(kF32Threads) void f32_dx_kernel(
+    const float* __restrict__ dG, const float* __restrict__ dU, const float* __restrict__ wg,
+    const float* __restrict__ wu, int P, int d, int f, int E, const int32_t* __restrict__ offsets,
+    float* __restrict__ dxp) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
+  if (i >= static_cast<size_t>(P) * d) return;
+  const int r = static_cast<int>(i / d), c = static_cast<int>(i % d);
+  const int e = expert_of_row(offsets, E, r);
+  const float* dg = dG + static_cast<size_t>(r) * f;
+  const float* du = dU + static_cast<size_t>(r) * f;
+  const float* g_col = wg + static_cast<size_t>(e) * f * d + c;
+  const float* u_col = wu + static_cast<size_t>(e) * f * d + c;
+  float s = 0.0f;
+  for (int n = 0; n < f; ++n) s = fmaf(dg[n], g_col[static_cast<size_t>(n) * d], s);
+  for (int n = 0; n < f; ++n) s = fmaf(du[n], u_col[static_cast<size_t>(n) * d], s);
+  dxp[i] = s;
+}
+
+// out[e][i][j] = sum over the expert's rows of lhs[r,i] * rhs[r,j]      one thread per (e,i,j)
+__global__ __launch_bounds__(kF32Threads) void f32_wgrad_kernel(
+    const float* __restrict__ lhs, int li, const float* __restrict__ rhs, int lj, int E, int P,
+    const int32_t* __restrict__ offsets, float* __restrict__ out) {
+  const size_t idx = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
+  const size_t per = static_cast<size_t>(li) * lj;
+  if (idx >= per * E) return;
+  const int e = static_cast<int>(idx / per);
+  const int i = static_cast<int>((idx % per) / lj), j = static_cast<int>(idx % lj);
+  float s = 0.0f;
+  const int begin = min(max(offsets[e], 0), P), end = min(offsets[e + 1], P);
+  for (int r = begin; r < end; ++r)
+    s = fmaf(lhs[static_cast<size_t>(r) * li + i], rhs[static_cast<size_t>(r) * lj + j], s);
+  out[idx] = s;
+}
+
+static unsigned blocks_for(size_t n) { return static_cast<unsigned>((n + kF32Threads - 1) / kF32Threads); }
+
+size_t ffn_fwd_ws_bytes_f32(int, int, int, int) { return 256; }
+
+size_t ffn_bwd_ws_bytes_f32(int P, int d, int f, int E, int have_saved) {
+  (void)d; (void)E;
+  const size_t pf = align_up(static_cast<size_t>(P) * f * sizeof(float), 256);
+  return 256 + (have_saved ? 2 : 4) * pf;     // dG, dU (+ recomputed G, U)
+}
+
+void ffn_fwd_f32(const FfnFwdArgs& a) {
+  const size_t pf = static_cast<size_t>(a.P) * a.f, pd = static_cast<size_t>(a.P) * a.d;
+  if (a.P == 0) return;
+  MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
+                     static_cast<const float*>(a.xp), static_cast<const float*>(a.w_gate),
+                     static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets,
+                     static_cast<float*>(a.g_save), static_cast<float*>(a.u_save), static_cast<float*>(a.act));
+  if (a.yp)
+    MOE_LAUNCH("f32_down", f32_down_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream,
+                       static_cast<const float*>(a.act), static_cast<const float*>(a.w_down), a.P, a.d, a.f, a.E,
+                       a.offsets, static_cast<float*>(a.yp));
+}
+
+void ffn_bwd_f32(const FfnBwdArgs& a) {
+  const size_t pf = static_cast<size_t>(a.P) * a.f, pd = static_cast<size_t>(a.P) * a.d;
+  const size_t pf_bytes = align_up(pf * sizeof(float), 256);
+  char* ws = static_cast<char*>(a.ws);
+  float* dG = reinterpret_cast<float*>(ws);
+  float* dU = reinterpret_cast<float*>(ws + pf_bytes);
+  const float* G = static_cast<const float*>(a.g_save);
+  const float* U = static_cast<const float*>(a.u_save);
+  if (a.P > 0) {
+    if (!G) {   // recompute the pre-activations
+      float* Gr = reinterpret_cast<float*>(ws + 2 * pf_bytes);
+      float* Ur = reinterpret_cast<float*>(ws + 3 * pf_bytes);
+      MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
+                         static_cast<const float*>(a.xp), static_cast<const float*>(a.w_gate),
+                         static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets, Gr, Ur,
+                         static_cast<float*>(nullptr));
+      G = Gr; U = Ur;
+    }
+    MOE_LAUNCH("f32_dact", f32_dact_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
+                       static_cast<const float*>(a.dyp), static_cast<const float*>(a.w_down), G, U, a.P, a.d, a.f, a.E,
+                       a.offsets, dG, dU);
+    MOE_LAUNCH("f32_dx", f32_dx_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream, dG, dU,
+                       static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E,
+                       a.offsets, static_cast<float*>(a.dxp));
+  }
+  const size_t per = static_cast<size_t>(a.d) * a.f * a.E;
+  // with P == 0 every segment is empty and the kernels only write zeros (dG/dU are not read)
+  MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream,
+                     static_cast<const float*>(a.dyp), a.d, static_cast<const float*>(a.act), a.f, a.E, a.P, a.offsets,
+                     static_cast<float*>(a.dw_down));
+  MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream,
+                     static_cast<const float*>(dG), a.f, static_cast<const float*>(a.xp), a.d, a.E, a.P, a.offsets,
+                     static_cast<float*>(a.dw_gate));
+  MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream,
+                     static_cast<const float*>(dU), a.f, static_cast<const float*>(a.xp), a.d, a.E, a.P, a.offsets,
+                     static_cast<float*>(a.dw_up));
+}
+
+}  // namespace moe

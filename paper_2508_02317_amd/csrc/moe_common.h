@@ -1,0 +1,102 @@
+// Shared host/device helpers of libmoe (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "moe.h"
+
+namespace moe {
+
+// ---- host-side error reporting ---------------------------------------------------------
+int32_t fail(int32_t code, const char* fmt, ...);   // records the message, returns code
+int32_t check_launch(const char* what);              // hipGetLastError -> MOE_ERR_HIP
+
+#define MOE_REQUIRE(cond, code, ...) \
+  do { if (!(cond)) return ::moe::fail((code), __VA_ARGS__); } while (0)
+
+// ---- optional per-kernel timing (HIP events on the launch stream) ----------------------------
+// Off by default; when moe_profile_enable(1) has been called every kernel launch is bracketed
+// by a pair of events recorded on the same stream, read back by moe_profile_report().
+struct ProfScope {
+  ProfScope(const char* name, hipStream_t stream);
+  ~ProfScope();
+  hipStream_t stream_;
+  int slot_;
+};
+#define MOE_LAUNCH(name, kern, grid, block, shmem, stream, ...)            \
+  do {                                                                     \
+    ::moe::ProfScope moe_prof_scope_(name, stream);                        \
+    hipLaunchKernelGGL(kern, grid, block, shmem, stream, __VA_ARGS__);     \
+  } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int elem_size(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+
+constexpr int kMaxExperts = 1024;
+constexpr int kMaxTopK = 64;
+
+// ---- bf16 <-> f32 on the device ---------------------------------------------------------
+typedef uint16_t bf16_t;   // raw bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+  return __uint_as_float(static_cast<uint32_t>(v) << 16);
+}
+// round to nearest, ties to even (inputs are finite on this path)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// fast variants (bf16 path: the result is rounded to 8 bits of mantissa anyway)
+__device__ __forceinline__ float sigmoid_fast(float g) { return 1.0f / (1.0f + __expf(-g)); }
+// accurate variants (fp32 path)
+__device__ __forceinline__ float sigmoid_acc(float g) { return 1.0f / (1.0f + expf(-g)); }
+
+// ---- wave64 reductions -------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// ---- internal launchers of the grouped expert FFN (one per element type) -------------------
+// All pointers are device pointers; arguments are already validated by the C entry points.
+struct FfnFwdArgs {
+  const void *xp, *w_gate, *w_up, *w_down;
+  int P, d, f, E;
+  const int32_t* offsets;
+  void *g_save, *u_save, *act, *yp;   // g_save/u_save/act may be null (not written then)
+  void* ws;
+  hipStream_t stream;
+};
+struct FfnBwdArgs {
+  const void *dyp, *xp, *g_save, *u_save, *act, *w_gate, *w_up, *w_down;
+  int P, d, f, E;
+  const int32_t* offsets;
+  void *dxp, *dw_gate, *dw_up, *dw_down;
+  void* ws;
+  hipStream_t stream;
+};
+size_t ffn_fwd_ws_bytes_bf16(int P, int d, int f, int E);
+size_t ffn_bwd_ws_bytes_bf16(int P, int d, int f, int E, int have_saved);
+void ffn_fwd_bf16(const FfnFwdArgs& a);
+void ffn_bwd_bf16(const FfnBwdArgs& a);
+size_t ffn_fwd_ws_bytes_f32(int P, int d, int f, int E);
+size_t ffn_bwd_ws_bytes_f32(int P, int d, int f, int E, int have_saved);
+void ffn_fwd_f32(const FfnFwdArgs& a);
+void ffn_bwd_f32(const FfnBwdArgs& a);
+
+}  // namespace moe

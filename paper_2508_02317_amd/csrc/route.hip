@@ -1,0 +1,311 @@
+// Top-k softmax routing and its backward (Sec. 3.2.3: tokens are routed to experts).
+//
+// One wavefront owns one token at a time.  Lane l holds the logits of experts l, l+64, ...
+// as 64-bit keys (order-preserving float bits in the high word, the complemented expert
+// index in the low word), so a single wave-wide max implements "largest logit, ties to
+// the lower index".  k rounds of that max give the slots in order.  Each workgroup keeps
+// an LDS histogram of the experts it selected and writes it to its own row of the
+// workspace; a second one-block kernel sums the rows (counts) and prefix-scans them
+// (offsets).  No float atomics, no global atomics: the result is deterministic.
+#include "moe_common.h"
+
+namespace moe {
+
+constexpr int kRouteThreads = 256;                 // 4 waves
+constexpr int kRouteWaves = kRouteThreads / 64;
+constexpr int kRouteMaxBlocks = 512;
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o) {
+  uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), o, 64);
+  uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), o, 64);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    uint64_t other = shfl_xor_u64(v, o);
+    v = other > v ? other : v;
+  }
+  return v;
+}
+// float -> uint32 whose unsigned order equals the float order (-0 folded into +0 first)
+__device__ __forceinline__ uint32_t ordered_bits(float f) {
+  uint32_t u = __float_as_uint(f + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered_bits(uint32_t o) {
+  uint32_t u = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
+  return __uint_as_float(u);
+}
+
+template <int VPL>   // logits held per lane; E <= 64 * VPL
+__global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
+    const float* __restrict__ logits, int T, int E, int k, int renorm,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int32_t* __restrict__ block_hist) {
+  __shared__ int32_t hist[kMaxExperts];
+  for (int e = threadIdx.x; e < E; e += kRouteThreads) hist[e] = 0;
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int waves_total = gridDim.x * kRouteWaves;
+  for (int t = blockIdx.x * kRouteWaves + wave; t < T; t += waves_total) {
+    const float* z = logits + static_cast<size_t>(t) * E;
+    uint64_t key[VPL];
+    float zloc[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      int e = lane + 64 * i;
+      if (e < E) {
+        zloc[i] = z[e] + 0.0f;
+        key[i] = (static_cast<uint64_t>(ordered_bits(zloc[i])) << 32) | static_cast<uint32_t>(~e);
+      } else {
+        zloc[i] = 0.0f;
+        key[i] = 0;   // below every real key (real keys have a non-zero low word)
+      }
+    }
+    int my_idx = 0;
+    float my_z = 0.0f;
+    float zmax = 0.0f;
+    for (int j = 0; j < k; ++j) {
+      uint64_t best = key[0];
+#pragma unroll
+      for (int i = 1; i < VPL; ++i) best = key[i] > best ? key[i] : best;
+      best = wave_max_u64(best);
+      int e_sel = static_cast<int>(~static_cast<uint32_t>(best));
+      float z_sel = from_ordered_bits(static_cast<uint32_t>(best >> 32));
+      if (j == 0) zmax = z_sel;
+      if (lane == j) { my_idx = e_sel; my_z = z_sel; }
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+        if (lane + 64 * i == e_sel) key[i] = 0;
+    }
+    // softmax weights: exp(z - max) over the selected (renorm) or over all experts
+    float ex = lane < k ? expf(my_z - zmax) : 0.0f;
+    float denom;
+    if (renorm) {
+      denom = wave_sum(ex);
+    } else {
+      float s = 0.0f;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+        if (lane + 64 * i < E) s += expf(zloc[i] - zmax);
+      denom = wave_sum(s);
+    }
+    if (lane < k) {
+      topk_idx[static_cast<size_t>(t) * k + lane] = my_idx;
+      topk_w[static_cast<size_t>(t) * k + lane] = ex / denom;
+      atomicAdd(&hist[my_idx], 1);
+    }
+  }
+  __syncthreads();
+  int32_t* out = block_hist + static_cast<size_t>(blockIdx.x) * E;
+  for (int e = threadIdx.x; e < E; e += kRouteThreads) out[e] = hist[e];
+}
+
+// counts[e] = sum over workgroup rows; offsets = exclusive scan.  One block of 1024 threads:
+// thread (g, c) sums rows g, g+G, ... of column c, then the groups are folded through LDS.
+__global__ __launch_bounds__(1024) void route_scan_kernel(
+    const int32_t* __restrict__ block_hist, int nblk, int E, int epad,
+    int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
+  __shared__ int32_t part[1024];
+  __shared__ int32_t scan[kMaxExperts];
+  const int groups = 1024 / epad;
+  const int c = threadIdx.x % epad;
+  const int g = threadIdx.x / epad;
+  int32_t s = 0;
+  if (c < E) {
+#pragma unroll 8
+    for (int b = g; b < nblk; b += groups) s += block_hist[static_cast<size_t>(b) * E + c];
+  }
+  part[threadIdx.x] = s;
+  __syncthreads();
+  if (g == 0) {
+    for (int q = 1; q < groups; ++q) s += part[q * epad + c];
+    scan[c] = c < E ? s : 0;
+    if (c < E) counts[c] = s;
+  }
+  __syncthreads();
+  // Hillis-Steele inclusive scan over epad (<= 1024) entries
+  for (int o = 1; o < epad; o <<= 1) {
+    int32_t v = 0;
+    if (threadIdx.x < epad && threadIdx.x >= o) v = scan[threadIdx.x - o];
+    __syncthreads();
+    if (threadIdx.x < epad) scan[threadIdx.x] += v;
+    __syncthreads();
+  }
+  if (threadIdx.x < E) offsets[threadIdx.x + 1] = scan[threadIdx.x];
+  if (threadIdx.x == 0) offsets[0] = 0;
+}
+
+// histogram of an already known assignment (pre-routed rows): same per-workgroup rows as above
+__global__ __launch_bounds__(kRouteThreads) void pair_hist_kernel(
+    const int32_t* __restrict__ idx, int n_pairs, int E, int32_t* __restrict__ block_hist) {
+  __shared__ int32_t hist[kMaxExperts];
+  for (int e = threadIdx.x; e < E; e += kRouteThreads) hist[e] = 0;
+  __syncthreads();
+  for (int p = blockIdx.x * kRouteThreads + threadIdx.x; p < n_pairs; p += gridDim.x * kRouteThreads) {
+    const int e = min(max(idx[p], 0), E - 1);
+    atomicAdd(&hist[e], 1);
+  }
+  __syncthreads();
+  int32_t* out = block_hist + static_cast<size_t>(blockIdx.x) * E;
+  for (int e = threadIdx.x; e < E; e += kRouteThreads) out[e] = hist[e];
+}
+
+template <int VPL>
+__global__ __launch_bounds__(kRouteThreads) void route_bwd_kernel(
+    const float* __restrict__ dw, const float* __restrict__ topk_w, const int32_t* __restrict__ topk_idx,
+    const float* __restrict__ logits, int T, int E, int k, int renorm, float* __restrict__ dlogits) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int waves_total = gridDim.x * kRouteWaves;
+  for (int t = blockIdx.x * kRouteWaves + wave; t < T; t += waves_total) {
+    int my_idx = -1;
+    float my_w = 0.0f, my_dw = 0.0f;
+    if (lane < k) {
+      my_idx = topk_idx[static_cast<size_t>(t) * k + lane];
+      my_w = topk_w[static_cast<size_t>(t) * k + lane];
+      my_dw = dw[static_cast<size_t>(t) * k + lane];
+    }
+    const float s = wave_sum(my_w * my_dw);          // sum_m w_m dw_m
+    const float my_val = my_w * (my_dw - s);          // value at a selected expert
+    float out[VPL];
+    if (renorm) {
+#pragma unroll
+      for (int i = 0; i < VPL; ++i) out[i] = 0.0f;
+    } else {
+      const float* z = logits + static_cast<size_t>(t) * E;
+      float zl[VPL];
+      float m = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i) {
+        int e = lane + 64 * i;
+        zl[i] = e < E ? z[e] : -INFINITY;
+        m = fmaxf(m, zl[i]);
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+      float sum = 0.0f;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i) {
+        zl[i] = (lane + 64 * i < E) ? expf(zl[i] - m) : 0.0f;
+        sum += zl[i];
+      }
+      sum = wave_sum(sum);
+#pragma unroll
+      for (int i = 0; i < VPL; ++i) out[i] = -(zl[i] / sum) * s;   // unselected: -p_e * s
+    }
+    for (int j = 0; j < k; ++j) {
+      int e_j = __shfl(my_idx, j, 64);
+      float v_j = __shfl(my_val, j, 64);
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+        if (lane + 64 * i == e_j) out[i] = v_j;
+    }
+    float* dz = dlogits + static_cast<size_t>(t) * E;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      int e = lane + 64 * i;
+      if (e < E) dz[e] = out[i];
+    }
+  }
+}
+
+static int route_blocks(int T) {
+  int b = ceil_div(T, kRouteWaves * 8);   // about 8 tokens per wave
+  return b < 1 ? 1 : (b > kRouteMaxBlocks ? kRouteMaxBlocks : b);
+}
+
+static int32_t check_route_dims(int T, int E, int k) {
+  MOE_REQUIRE(T >= 0 && E > 0 && k > 0, MOE_ERR_INVALID_ARG, "route: need T >= 0, E > 0, k > 0 (T=%d E=%d k=%d)", T, E, k);
+  MOE_REQUIRE(k <= E, MOE_ERR_INVALID_ARG, "route: k=%d exceeds E=%d", k, E);
+  MOE_REQUIRE(E <= kMaxExperts, MOE_ERR_UNSUPPORTED, "route: E=%d above the built maximum %d", E, kMaxExperts);
+  MOE_REQUIRE(k <= kMaxTopK, MOE_ERR_UNSUPPORTED, "route: k=%d above the built maximum %d", k, kMaxTopK);
+  MOE_REQUIRE(static_cast<int64_t>(T) * k <= INT32_MAX, MOE_ERR_UNSUPPORTED, "route: T*k does not fit in int32");
+  return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" size_t moe_route_topk_workspace_bytes(int T, int E, int k) {
+  (void)k;
+  if (T < 0 || E <= 0) return 0;
+  return align_up(static_cast<size_t>(route_blocks(T)) * E * sizeof(int32_t), 256);
+}
+
+extern "C" int32_t moe_route_topk(const float* logits, int T, int E, int k, int renorm,
+                                  int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_route_dims(T, E, k)) return rc;
+  MOE_REQUIRE(counts && offsets, MOE_ERR_INVALID_ARG, "route: counts/offsets must not be null");
+  MOE_REQUIRE(T == 0 || (logits && topk_idx && topk_w), MOE_ERR_INVALID_ARG, "route: null logits/topk_idx/topk_w");
+  MOE_REQUIRE(ws && ws_bytes >= moe_route_topk_workspace_bytes(T, E, k), MOE_ERR_WORKSPACE,
+              "route: workspace null or smaller than %zu bytes", moe_route_topk_workspace_bytes(T, E, k));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int nblk = route_blocks(T);
+  int32_t* hist = static_cast<int32_t*>(ws);
+  const int vpl = ceil_div(E, 64);
+#define MOE_LAUNCH_ROUTE(V) \
+  MOE_LAUNCH("route_topk", route_topk_kernel<V>, dim3(nblk), dim3(kRouteThreads), 0, s, logits, T, E, k, renorm, topk_idx, topk_w, hist)
+  if (vpl <= 1) MOE_LAUNCH_ROUTE(1);
+  else if (vpl <= 2) MOE_LAUNCH_ROUTE(2);
+  else if (vpl <= 4) MOE_LAUNCH_ROUTE(4);
+  else if (vpl <= 8) MOE_LAUNCH_ROUTE(8);
+  else MOE_LAUNCH_ROUTE(16);
+#undef MOE_LAUNCH_ROUTE
+  int epad = 64;
+  while (epad < E) epad <<= 1;
+  MOE_LAUNCH("route_scan", route_scan_kernel, dim3(1), dim3(1024), 0, s, hist, nblk, E, epad, counts, offsets);
+  return check_launch("moe_route_topk");
+}
+
+static int hist_blocks(int n_pairs) {
+  int b = ceil_div(n_pairs, kRouteThreads * 4);
+  return b < 1 ? 1 : (b > kRouteMaxBlocks ? kRouteMaxBlocks : b);
+}
+
+extern "C" size_t moe_expert_offsets_workspace_bytes(int n_pairs, int E) {
+  if (n_pairs < 0 || E <= 0) return 0;
+  return align_up(static_cast<size_t>(hist_blocks(n_pairs)) * E * sizeof(int32_t), 256);
+}
+
+extern "C" int32_t moe_expert_offsets(const int32_t* topk_idx, int n_pairs, int E, int32_t* counts,
+                                      int32_t* offsets, void* ws, size_t ws_bytes, void* stream) {
+  MOE_REQUIRE(n_pairs >= 0 && E > 0, MOE_ERR_INVALID_ARG, "expert_offsets: need n_pairs >= 0, E > 0");
+  MOE_REQUIRE(E <= kMaxExperts, MOE_ERR_UNSUPPORTED, "expert_offsets: E=%d above the built maximum %d", E, kMaxExperts);
+  MOE_REQUIRE(counts && offsets && (n_pairs == 0 || topk_idx), MOE_ERR_INVALID_ARG, "expert_offsets: null pointer");
+  MOE_REQUIRE(ws && ws_bytes >= moe_expert_offsets_workspace_bytes(n_pairs, E), MOE_ERR_WORKSPACE,
+              "expert_offsets: workspace null or smaller than %zu bytes", moe_expert_offsets_workspace_bytes(n_pairs, E));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int nblk = hist_blocks(n_pairs);
+  int32_t* hist = static_cast<int32_t*>(ws);
+  MOE_LAUNCH("pair_hist", pair_hist_kernel, dim3(nblk), dim3(kRouteThreads), 0, s, topk_idx, n_pairs, E, hist);
+  int epad = 64;
+  while (epad < E) epad <<= 1;
+  MOE_LAUNCH("route_scan", route_scan_kernel, dim3(1), dim3(1024), 0, s, hist, nblk, E, epad, counts, offsets);
+  return check_launch("moe_expert_offsets");
+}
+
+extern "C" int32_t moe_route_topk_bwd(const float* dw, const float* topk_w, const int32_t* topk_idx,
+                                      const float* logits, int T, int E, int k, int renorm,
+                                      float* dlogits, void* stream) {
+  if (int32_t rc = check_route_dims(T, E, k)) return rc;
+  if (T == 0) return MOE_OK;
+  MOE_REQUIRE(dw && topk_w && topk_idx && dlogits, MOE_ERR_INVALID_ARG, "route_bwd: null pointer");
+  MOE_REQUIRE(renorm || logits, MOE_ERR_INVALID_ARG, "route_bwd: logits required when renorm == 0");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int nblk = route_blocks(T);
+  const int vpl = ceil_div(E, 64);
+#define MOE_LAUNCH_RBWD(V) \
+  MOE_LAUNCH("route_bwd", route_bwd_kernel<V>, dim3(nblk), dim3(kRouteThreads), 0, s, dw, topk_w, topk_idx, logits, T, E, k, renorm, dlogits)
+  if (vpl <= 1) MOE_LAUNCH_RBWD(1);
+  else if (vpl <= 2) MOE_LAUNCH_RBWD(2);
+  else if (vpl <= 4) MOE_LAUNCH_RBWD(4);
+  else if (vpl <= 8) MOE_LAUNCH_RBWD(8);
+  else MOE_LAUNCH_RBWD(16);
+#undef MOE_LAUNCH_RBWD
+  return check_launch("moe_route_topk_bwd");
+}

@@ -1,0 +1,261 @@
+"""ctypes binding of libmoe_gfx950.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/moe.h) and does
+nothing but check tensor dtypes / contiguity, allocate outputs and workspaces with torch
+when the caller did not pass them, and hand raw device pointers and the current HIP
+stream to the library.  All arithmetic of the MoE layer runs inside the library's
+kernels.  There is no fallback: if the shared library has not been built, importing this
+module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_gfx950.so")
+
+MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP = range(5)
+MOE_F32, MOE_BF16 = 0, 1
+
+EXPORTS = [
+    "moe_version", "moe_last_error",
+    "moe_route_topk_workspace_bytes", "moe_route_topk", "moe_route_topk_bwd",
+    "moe_expert_offsets_workspace_bytes", "moe_expert_offsets",
+    "moe_permute_workspace_bytes", "moe_permute",
+    "moe_grouped_gemm_swiglu_fwd_workspace_bytes", "moe_grouped_gemm_swiglu_fwd",
+    "moe_grouped_gemm_swiglu_bwd_workspace_bytes", "moe_grouped_gemm_swiglu_bwd",
+    "moe_unpermute_combine_fwd", "moe_unpermute_combine_bwd",
+    "moe_profile_enable", "moe_profile_report",
+]
+
+
+class MoEError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("libmoe status %d: %s" % (code, message))
+        self.code = code
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libmoe_gfx950.so is not built (%s missing). Build it with "
+            "`python -m paper_2508_02317_amd.build`; there is no fallback path." % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.moe_version.restype = ctypes.c_char_p
+    lib.moe_version.argtypes = []
+    lib.moe_last_error.restype = ctypes.c_char_p
+    lib.moe_last_error.argtypes = []
+    lib.moe_route_topk_workspace_bytes.restype = sz
+    lib.moe_route_topk_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.moe_route_topk.restype = ctypes.c_int32
+    lib.moe_route_topk.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_route_topk_bwd.restype = ctypes.c_int32
+    lib.moe_route_topk_bwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.moe_expert_offsets_workspace_bytes.restype = sz
+    lib.moe_expert_offsets_workspace_bytes.argtypes = [i32, i32]
+    lib.moe_expert_offsets.restype = ctypes.c_int32
+    lib.moe_expert_offsets.argtypes = [vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.moe_permute_workspace_bytes.restype = sz
+    lib.moe_permute_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.moe_permute.restype = ctypes.c_int32
+    lib.moe_permute.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_grouped_gemm_swiglu_fwd_workspace_bytes.restype = sz
+    lib.moe_grouped_gemm_swiglu_fwd_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.moe_grouped_gemm_swiglu_fwd.restype = ctypes.c_int32
+    lib.moe_grouped_gemm_swiglu_fwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_grouped_gemm_swiglu_bwd_workspace_bytes.restype = sz
+    lib.moe_grouped_gemm_swiglu_bwd_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.moe_grouped_gemm_swiglu_bwd.restype = ctypes.c_int32
+    lib.moe_grouped_gemm_swiglu_bwd.argtypes = [vp] * 8 + [i32] * 5 + [vp] * 6 + [sz, vp]
+    lib.moe_unpermute_combine_fwd.restype = ctypes.c_int32
+    lib.moe_unpermute_combine_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.moe_unpermute_combine_bwd.restype = ctypes.c_int32
+    lib.moe_unpermute_combine_bwd.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.moe_profile_enable.restype = ctypes.c_int32
+    lib.moe_profile_enable.argtypes = [i32]
+    lib.moe_profile_report.restype = sz
+    lib.moe_profile_report.argtypes = [ctypes.c_char_p, sz]
+    return lib
+
+
+lib = _load()
+
+
+def moe_version():
+    return lib.moe_version().decode()
+
+
+def moe_last_error():
+    return lib.moe_last_error().decode()
+
+
+def moe_profile_enable(on):
+    _check(lib.moe_profile_enable(int(bool(on))))
+
+
+def moe_profile_report():
+    """-> {kernel name: (launches, total milliseconds)} since the last report."""
+    buf = ctypes.create_string_buffer(1 << 16)
+    lib.moe_profile_report(buf, len(buf))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, count, ms = line.split()
+        out[name] = (int(count), float(ms))
+    return out
+
+
+def _check(status):
+    if status != MOE_OK:
+        raise MoEError(status, moe_last_error())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return MOE_F32
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    raise TypeError("libmoe supports float32 and bfloat16 tensors, got %s" % t.dtype)
+
+
+def _need(t, dtype=None, name="tensor"):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous device tensor" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    return t
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes, ws, device):
+    if ws is None:
+        ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    return ws, ws.numel()
+
+
+# --------------------------------------------------------------------------------------------
+
+def moe_route_topk(logits, k, renorm=1, out=None, ws=None):
+    """-> topk_idx [T,k] i32, topk_w [T,k] f32, counts [E] i32, offsets [E+1] i32."""
+    _need(logits, torch.float32, "logits")
+    T, E = logits.shape
+    dev = logits.device
+    if out is None:
+        out = (torch.empty((T, k), dtype=torch.int32, device=dev), torch.empty((T, k), dtype=torch.float32, device=dev),
+               torch.empty(E, dtype=torch.int32, device=dev), torch.empty(E + 1, dtype=torch.int32, device=dev))
+    idx, w, counts, offsets = out
+    ws, nbytes = _ws(lib.moe_route_topk_workspace_bytes(T, E, k), ws, dev)
+    _check(lib.moe_route_topk(_ptr(logits), T, E, k, int(renorm), _ptr(idx), _ptr(w), _ptr(counts), _ptr(offsets),
+                              _ptr(ws), nbytes, _stream()))
+    return idx, w, counts, offsets
+
+
+def moe_expert_offsets(topk_idx, E, out=None, ws=None):
+    """-> counts [E] i32, offsets [E+1] i32 of a known assignment."""
+    _need(topk_idx, torch.int32, "topk_idx")
+    n = topk_idx.numel()
+    dev = topk_idx.device
+    if out is None:
+        out = (torch.empty(E, dtype=torch.int32, device=dev), torch.empty(E + 1, dtype=torch.int32, device=dev))
+    counts, offsets = out
+    ws, nbytes = _ws(lib.moe_expert_offsets_workspace_bytes(n, E), ws, dev)
+    _check(lib.moe_expert_offsets(_ptr(topk_idx), n, E, _ptr(counts), _ptr(offsets), _ptr(ws), nbytes, _stream()))
+    return counts, offsets
+
+
+def moe_route_topk_bwd(dw, topk_w, topk_idx, logits, E, renorm=1, out=None):
+    """-> dlogits [T,E] f32."""
+    _need(dw, torch.float32, "dw"); _need(topk_w, torch.float32, "topk_w"); _need(topk_idx, torch.int32, "topk_idx")
+    T, k = topk_idx.shape
+    if out is None:
+        out = torch.empty((T, E), dtype=torch.float32, device=dw.device)
+    _check(lib.moe_route_topk_bwd(_ptr(dw), _ptr(topk_w), _ptr(topk_idx), _ptr(logits), T, E, k, int(renorm),
+                                  _ptr(out), _stream()))
+    return out
+
+
+def moe_permute(x, topk_idx, offsets, E, out=None, ws=None):
+    """-> xp [P,d], row_of_pair [P] i32, pair_of_row [P] i32."""
+    _need(x, None, "x"); _need(topk_idx, torch.int32, "topk_idx"); _need(offsets, torch.int32, "offsets")
+    T, d = x.shape
+    k = topk_idx.shape[1]
+    P = T * k
+    if out is None:
+        out = (torch.empty((P, d), dtype=x.dtype, device=x.device), torch.empty(P, dtype=torch.int32, device=x.device),
+               torch.empty(P, dtype=torch.int32, device=x.device))
+    xp, row_of_pair, pair_of_row = out
+    ws, nbytes = _ws(lib.moe_permute_workspace_bytes(T, E, k), ws, x.device)
+    _check(lib.moe_permute(_ptr(x), _dtype_code(x), T, d, E, k, _ptr(topk_idx), _ptr(offsets), _ptr(xp),
+                           _ptr(row_of_pair), _ptr(pair_of_row), _ptr(ws), nbytes, _stream()))
+    return xp, row_of_pair, pair_of_row
+
+
+def moe_grouped_gemm_swiglu_fwd(xp, w_gate, w_up, w_down, offsets, save_gu=True, out=None, ws=None):
+    """-> act [P,f], yp [P,d], g_save, u_save ([P,f] or None)."""
+    _need(xp, None, "xp"); _need(offsets, torch.int32, "offsets")
+    for name, w in (("w_gate", w_gate), ("w_up", w_up), ("w_down", w_down)):
+        _need(w, xp.dtype, name)
+    P, d = xp.shape
+    E, f, _ = w_gate.shape
+    dev = xp.device
+    if out is None:
+        mk = lambda *s: torch.empty(s, dtype=xp.dtype, device=dev)
+        out = (mk(P, f), mk(P, d), mk(P, f) if save_gu else None, mk(P, f) if save_gu else None)
+    act, yp, g, u = out
+    code = _dtype_code(xp)
+    ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_fwd_workspace_bytes(code, P, d, f, E), ws, dev)
+    _check(lib.moe_grouped_gemm_swiglu_fwd(_ptr(xp), _ptr(w_gate), _ptr(w_up), _ptr(w_down), code, P, d, f, E,
+                                           _ptr(offsets), _ptr(g), _ptr(u), _ptr(act), _ptr(yp), _ptr(ws), nbytes,
+                                           _stream()))
+    return act, yp, g, u
+
+
+def moe_grouped_gemm_swiglu_bwd(dyp, xp, g_save, u_save, act, w_gate, w_up, w_down, offsets, out=None, ws=None):
+    """-> dxp [P,d], dw_gate [E,f,d], dw_up [E,f,d], dw_down [E,d,f]."""
+    _need(dyp, xp.dtype, "dyp"); _need(xp, None, "xp"); _need(act, xp.dtype, "act")
+    P, d = xp.shape
+    E, f, _ = w_gate.shape
+    if out is None:
+        out = (torch.empty_like(xp), torch.empty_like(w_gate), torch.empty_like(w_up), torch.empty_like(w_down))
+    dxp, dwg, dwu, dwd = out
+    code = _dtype_code(xp)
+    have_saved = int(g_save is not None)
+    ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_bwd_workspace_bytes(code, P, d, f, E, have_saved), ws, xp.device)
+    _check(lib.moe_grouped_gemm_swiglu_bwd(_ptr(dyp), _ptr(xp), _ptr(g_save), _ptr(u_save), _ptr(act), _ptr(w_gate),
+                                           _ptr(w_up), _ptr(w_down), code, P, d, f, E, _ptr(offsets), _ptr(dxp),
+                                           _ptr(dwg), _ptr(dwu), _ptr(dwd), _ptr(ws), nbytes, _stream()))
+    return dxp, dwg, dwu, dwd
+
+
+def moe_unpermute_combine_fwd(yp, topk_w, row_of_pair, T, k, out=None):
+    """-> y [T,d]; topk_w None = unit weights (backward of moe_permute)."""
+    _need(yp, None, "yp"); _need(row_of_pair, torch.int32, "row_of_pair")
+    if topk_w is not None:
+        _need(topk_w, torch.float32, "topk_w")
+    d = yp.shape[1]
+    if out is None:
+        out = torch.empty((T, d), dtype=yp.dtype, device=yp.device)
+    _check(lib.moe_unpermute_combine_fwd(_ptr(yp), _dtype_code(yp), T, d, k, _ptr(topk_w), _ptr(row_of_pair),
+                                         _ptr(out), _stream()))
+    return out
+
+
+def moe_unpermute_combine_bwd(dy, yp, topk_w, row_of_pair, out=None):
+    """-> dyp [P,d], dw [T,k] f32."""
+    _need(dy, yp.dtype, "dy"); _need(yp, None, "yp"); _need(topk_w, torch.float32, "topk_w")
+    T, d = dy.shape
+    k = topk_w.shape[1]
+    if out is None:
+        out = (torch.empty_like(yp), torch.empty((T, k), dtype=torch.float32, device=dy.device))
+    dyp, dw = out
+    _check(lib.moe_unpermute_combine_bwd(_ptr(dy), _ptr(yp), _dtype_code(yp), T, d, k, _ptr(topk_w), _ptr(row_of_pair),
+                                         _ptr(dyp), _ptr(dw), _stream()))
+    return dyp, dw

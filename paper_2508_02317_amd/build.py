@@ -54,4 +54,4 @@ def build_library(verbose=False, extra_flags=()):
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, extra_flags=tuple(sys.argv[1:])))

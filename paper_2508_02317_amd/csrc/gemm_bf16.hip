@@ -5,9 +5,14 @@
 //   * a BM x BN output tile per 256-thread workgroup: 2 x 2 wavefronts, each owning a
 //     WM x WN sub-tile made of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, fp32
 //     accumulators kept in registers for the whole reduction);
-//   * the reduction dimension is walked in BK-wide slabs, double-buffered in LDS; the
-//     global loads of slab i+1 are issued before the MFMAs of slab i, and one barrier
-//     per slab separates writers from readers;
+//   * the reduction dimension is walked in BK-wide slabs through a 3-stage LDS ring that is
+//     filled by direct global->LDS loads (no staging registers); two to three slabs are in
+//     flight behind the one being multiplied, the MFMA operands are double-buffered in
+//     registers one reduction step ahead, and one barrier per slab separates writers from
+//     readers;
+//   * results leave through LDS as well, so that all global stores (and the loads of the
+//     saved pre-activations in the fused SwiGLU derivative) are 16 bytes per lane and
+//     contiguous along rows;
 //   * an operand whose reduction index is contiguous in memory is staged as
 //     [rows][BK] and read with 16-byte LDS loads; an operand whose reduction index is the
 //     slow axis in memory (the weight in the two backward-data products, both operands of
@@ -40,7 +45,9 @@ struct Tile {
   static constexpr int WM = BM / 2, WN = BN / 2;          // 2 x 2 waves
   static constexpr int MI = WM / 32, NI = WN / 32;        // MFMA tiles per wave
   static constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2;
-  static constexpr int kLdsBytes = 2 * (kABytes + kBBytes);
+  static constexpr int kStageBytes = kABytes + kBBytes;
+  static constexpr int kStages = 3;                       // LDS ring: two slabs in flight, one being read
+  static constexpr int kLdsBytes = kStages * kStageBytes;
 };
 
 // One operand tile of ROWS rows: element (row, k).  Two halves of ROWS/2 rows with their own
@@ -161,73 +168,231 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
   }
 }
 
+// ---- global -> LDS without passing through registers -----------------------------------------------
+// One wave instruction (global_load_lds_dwordx4) moves 64 x 16 bytes into 1 KiB of consecutive LDS;
+// the swizzles above are applied on the global side: each lane fetches the piece that belongs in its
+// LDS slot.  Rows that do not exist are redirected to the tile's first row: they only feed output
+// rows / columns that are never stored.  The reduction range is NOT checked here, so this path is
+// used for full slabs only; a partial last slab goes through the register Stager, which zero-fills.
+template <bool KS, int ROWS, int BK> struct Dma {
+  static constexpr int CHUNKS = ROWS * BK * 2 / 1024;
+  static constexpr int N = CHUNKS / 4;                       // chunks per wave
+  const bf16_t* ptr[N];
+  long step;                                                 // elements per slab
+  __device__ __forceinline__ void init(const Operand& op, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = wave * N + i;
+      if constexpr (!KS) {
+        constexpr int PPR = BK / 8, RPC = 1024 / (BK * 2), RPL = 256 / (BK * 2);
+        const int row = c * RPC + lane / PPR;
+        const int piece = (lane % PPR) ^ ((row / RPL) & (PPR - 1));
+        const bool upper = row >= ROWS / 2;
+        const int rh = row - (upper ? ROWS / 2 : 0);
+        const bool ok = rh < (upper ? op.valid[1] : op.valid[0]);
+        const bf16_t* base = ok ? (upper ? op.half[1] : op.half[0]) + static_cast<long>(rh) * op.ld : op.half[0];
+        ptr[i] = base + piece * 8;
+      } else {
+        constexpr int PPK = ROWS / 8, KPC = 1024 / (ROWS * 2);
+        const int k = c * KPC + lane / PPK;
+        const int phys = lane % PPK;
+        const int piece = ((((phys >> 2) ^ (k & 3)) << 2) | (phys & 3));
+        const int col = piece * 8;
+        const bool upper = col >= ROWS / 2;
+        const int ch = col - (upper ? ROWS / 2 : 0);
+        const bool ok = ch < (upper ? op.valid[1] : op.valid[0]);
+        ptr[i] = (ok ? (upper ? op.half[1] : op.half[0]) + ch : op.half[0]) + static_cast<long>(k) * op.ld;
+      }
+    }
+    step = KS ? static_cast<long>(BK) * op.ld : BK;
+  }
+  // enqueue this wave's share of slab `slab` into the operand tile at `tile` (LDS)
+  __device__ __forceinline__ void issue(int slab, char* tile, int wave) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+#ifdef MOE_DBG_NO_LOAD
+      if (slab > 0) continue;
+#endif
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(ptr[i] + slab * step),
+          (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
+    }
+  }
+};
+
+// s_waitcnt that waits only for the vector-memory counter to drop to n (gfx9 encoding:
+// vmcnt = imm[3:0] | imm[15:14] << 4, expcnt = imm[6:4], lgkmcnt = imm[11:8])
+template <int n> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14));
+}
+
+// s_waitcnt that waits only for the LDS / scalar-memory counter to reach zero
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14)); }
+
+// the MFMA operands of one 16-wide reduction step for this wave's sub-tile
+template <class T> struct Frags {
+  bf16x8 a[T::MI];
+  bf16x8 b[T::NI];
+};
+template <class T, bool A_KS, bool B_KS>
+__device__ __forceinline__ void load_frags(Frags<T>& f, const char* bufA, const char* bufB, int kk,
+                                           const int (&a_row)[T::MI], const int (&b_row)[T::NI], int lane) {
+#pragma unroll
+  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM, T::BK>(bufA, a_row[i], kk, lane);
+#pragma unroll
+  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN, T::BK>(bufB, b_row[i], kk, lane);
+}
+template <class T>
+__device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::NI]) {
+#pragma unroll
+  for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < T::NI; ++ni)
+      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+}
+
 // acc += sum over segments of A_s(BM x K) * B_s(BN x K)^T for this wave's sub-tile (segments differ
-// only in their base pointers), operands staged
-// through LDS.  a_row[mi] / b_row[ni]: first tile row of the wave's mi-th / ni-th 32-row fragment.
-// Every slab ends with a barrier, so the next segment can start writing LDS right away.
+// only in their base pointers).  a_row[mi] / b_row[ni]: first tile row of the wave's mi-th / ni-th
+// 32-row fragment.
+//
+// Full slabs stream through a 3-stage LDS ring filled by direct global->LDS loads, and the MFMA
+// operands are double-buffered in registers, so that every LDS read is issued one reduction step
+// ahead of the MFMAs that consume it.  Per slab kt:
+//     read step 1.. of slab kt (into the other register set) | MFMAs of the steps already loaded
+//     wait: own LDS reads of slab kt complete, own loads of slab kt+1 landed
+//     barrier: slab kt+1 is visible to all, and nobody reads the stage of slab kt any more
+//     refill that stage with slab kt+3; read step 0 of slab kt+1 | MFMAs of the last step of slab kt
+// so two to three slabs are in flight behind the slab being multiplied.
 template <class T, bool A_KS, bool B_KS>
 __device__ __forceinline__ void mainloop(const Operand* opA, const Operand* opB, int nseg, int K, char* lds,
                                          const int (&a_row)[T::MI], const int (&b_row)[T::NI],
                                          f32x16 (&acc)[T::MI][T::NI]) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int ktiles = (K + T::BK - 1) / T::BK;
-  if (ktiles <= 0) return;
-  char* const tA = lds;                              // two A buffers, then two B buffers
-  char* const tB = lds + 2 * T::kABytes;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (K <= 0) return;
+  const int nfull = K / T::BK;
+  const int tail = K - nfull * T::BK;
+  typedef Dma<A_KS, T::BM, T::BK> DmaA;
+  typedef Dma<B_KS, T::BN, T::BK> DmaB;
+  constexpr int L = DmaA::N + DmaB::N;                 // loads per thread per slab
+  constexpr int STEPS = T::BK / 16;                    // reduction steps per slab (even)
 #pragma nounroll
   for (int seg = 0; seg < nseg; ++seg) {
-    Stager<A_KS, T::BM, T::BK> sa;
-    Stager<B_KS, T::BN, T::BK> sb;
-    {   // pick the segment's operands field by field: no dynamically indexed copies
-      Operand oa, ob;
-      oa.half[0] = seg ? opA[1].half[0] : opA[0].half[0];
-      oa.half[1] = seg ? opA[1].half[1] : opA[0].half[1];
-      oa.ld = opA[0].ld;
-      oa.valid[0] = opA[0].valid[0];
-      oa.valid[1] = opA[0].valid[1];
-      ob.half[0] = seg ? opB[1].half[0] : opB[0].half[0];
-      ob.half[1] = seg ? opB[1].half[1] : opB[0].half[1];
-      ob.ld = opB[0].ld;
-      ob.valid[0] = opB[0].valid[0];
-      ob.valid[1] = opB[0].valid[1];
+    Operand oa, ob;                                    // picked field by field: no dynamically indexed copies
+    oa.half[0] = seg ? opA[1].half[0] : opA[0].half[0];
+    oa.half[1] = seg ? opA[1].half[1] : opA[0].half[1];
+    oa.ld = opA[0].ld;
+    oa.valid[0] = opA[0].valid[0];
+    oa.valid[1] = opA[0].valid[1];
+    ob.half[0] = seg ? opB[1].half[0] : opB[0].half[0];
+    ob.half[1] = seg ? opB[1].half[1] : opB[0].half[1];
+    ob.ld = opB[0].ld;
+    ob.valid[0] = opB[0].valid[0];
+    ob.valid[1] = opB[0].valid[1];
+    if (nfull > 0) {
+      DmaA da;
+      DmaB db;
+      da.init(oa, wave, lane);
+      db.init(ob, wave, lane);
+#pragma unroll
+      for (int s0 = 0; s0 < 3; ++s0)
+        if (s0 < nfull) {
+          da.issue(s0, lds + s0 * T::kStageBytes, wave);
+          db.issue(s0, lds + s0 * T::kStageBytes + T::kABytes, wave);
+        }
+      if (nfull > 2) wait_vmcnt<2 * L>(); else if (nfull > 1) wait_vmcnt<L>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      Frags<T> f0, f1;                                 // even / odd reduction steps
+      load_frags<T, A_KS, B_KS>(f0, lds, lds + T::kABytes, 0, a_row, b_row, lane);
+      int stage = 0;
+#pragma nounroll
+      for (int kt = 0; kt < nfull; ++kt) {
+        char* buf = lds + stage * T::kStageBytes;
+#pragma unroll
+        for (int kk = 0; kk + 2 < STEPS; kk += 2) {    // all but the last two steps of the slab
+          load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, kk + 1, a_row, b_row, lane);
+          mma<T>(f0, acc);
+          load_frags<T, A_KS, B_KS>(f0, buf, buf + T::kABytes, kk + 2, a_row, b_row, lane);
+          mma<T>(f1, acc);
+        }
+        load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, STEPS - 1, a_row, b_row, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        mma<T>(f0, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_lgkmcnt0();                               // this wave no longer needs the stage of slab kt
+        if (kt + 1 < nfull) {
+          if (kt + 2 < nfull) wait_vmcnt<L>(); else wait_vmcnt<0>();
+        }
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 3 < nfull) {
+          da.issue(kt + 3, buf, wave);
+          db.issue(kt + 3, buf + T::kABytes, wave);
+        }
+        stage = stage == 2 ? 0 : stage + 1;
+        if (kt + 1 < nfull) {
+          const char* nxt = lds + stage * T::kStageBytes;
+          load_frags<T, A_KS, B_KS>(f0, nxt, nxt + T::kABytes, 0, a_row, b_row, lane);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mma<T>(f1, acc);
+      }
+    }
+    if (tail) {
+      // partial last slab: through registers, zero-filled beyond K.  Every stage is free here: all
+      // loads have landed and every wave finished its LDS reads before the last barrier.
+      Stager<A_KS, T::BM, T::BK> sa;
+      Stager<B_KS, T::BN, T::BK> sb;
       sa.init(oa, tid);
       sb.init(ob, tid);
-    }
-    sa.load(0, K);
-    sb.load(0, K);
-    sa.store(tA);
-    sb.store(tB);
-    __syncthreads();
-#pragma nounroll
-    for (int kt = 0; kt < ktiles; ++kt) {
-      const int cur = kt & 1;
-      const bool more = kt + 1 < ktiles;
-      if (more) {
-        sa.load((kt + 1) * T::BK, K);
-        sb.load((kt + 1) * T::BK, K);
-      }
-      const char* bufA = tA + cur * T::kABytes;
-      const char* bufB = tB + cur * T::kBBytes;
-#pragma unroll
-      for (int kk = 0; kk < T::BK / 16; ++kk) {
-        bf16x8 a[T::MI], b[T::NI];
-#pragma unroll
-        for (int i = 0; i < T::MI; ++i) a[i] = read_frag<A_KS, T::BM, T::BK>(bufA, a_row[i], kk, lane);
-#pragma unroll
-        for (int i = 0; i < T::NI; ++i) b[i] = read_frag<B_KS, T::BN, T::BK>(bufB, b_row[i], kk, lane);
-#pragma unroll
-        for (int mi = 0; mi < T::MI; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < T::NI; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-      }
-      if (more) {
-        sa.store(tA + (cur ^ 1) * T::kABytes);
-        sb.store(tB + (cur ^ 1) * T::kBBytes);
-      }
+      sa.load(nfull * T::BK, K);
+      sb.load(nfull * T::BK, K);
+      sa.store(lds);
+      sb.store(lds + T::kABytes);
       __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < STEPS; ++kk) {
+        Frags<T> f;
+        load_frags<T, A_KS, B_KS>(f, lds, lds + T::kABytes, kk, a_row, b_row, lane);
+        mma<T>(f, acc);
+      }
     }
+    __syncthreads();                                   // all reads done before anything refills the ring
   }
+}
+
+// element i (0..15) of a 32x32 MFMA tile held by `lane`: row 8*(i/4) + 4*(lane/32) + i%4, col lane%32
+__device__ __forceinline__ int acc_row(int lane, int i) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
+
+// ---- epilogue: accumulators -> LDS (fp32) -> 16-byte row-contiguous global accesses -----------------
+// The MFMA result layout gives a lane one column and four consecutive rows; written out directly
+// that means 2-byte accesses.  Each wave instead parks a 32-row strip of its sub-tile in its own
+// quarter of the (now idle) LDS ring and reads it back row-major, 8 consecutive columns per lane.
+template <class T> struct Strip {
+  static constexpr int LD = T::WN + 8;                 // floats per staged row: 4 rows shift the banks by 32
+  static constexpr int kBytes = 32 * LD * 4;
+  static_assert(4 * kBytes <= T::kLdsBytes, "staging strips must fit in the LDS ring");
+};
+
+template <class T>
+__device__ __forceinline__ void park_strip(const f32x16 (&acc_mi)[T::NI], float* strip, int lane) {
+#pragma unroll
+  for (int ni = 0; ni < T::NI; ++ni)
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      strip[acc_row(lane, i) * Strip<T>::LD + ni * 32 + (lane & 31)] = acc_mi[ni][i];
+}
+
+__device__ __forceinline__ void read8(const float* p, float (&v)[8]) {
+  const float4 x = *reinterpret_cast<const float4*>(p), y = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+}
+__device__ __forceinline__ uint4 pack8(const float (&v)[8]) {
+  return make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+}
+__device__ __forceinline__ void unpack8(const uint4& w, float (&v)[8]) {
+  v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
+  v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
 }
 
 // ---- device-built schedule of (expert, row tile) for row-grouped products -----------------
@@ -272,8 +437,6 @@ __device__ __forceinline__ int xcd_remap(int b, int total) {
   return (b / kXcds < per && v < total) ? v : -1;
 }
 
-// element i (0..15) of a 32x32 MFMA tile held by `lane`: row 8*(i/4) + 4*(lane/32) + i%4, col lane%32
-__device__ __forceinline__ int acc_row(int lane, int i) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
 
 template <class T>
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[T::MI][T::NI]) {
@@ -355,24 +518,32 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
     opB.half[1] = p.w1 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.valid[0] = opB.valid[1] = ncols;
     mainloop<T, false, false>(opsA, opsB, 1, p.K, lds, a_row, b_row, acc);
+    // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
+    float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+    constexpr int LPR = HW / 8;                        // lanes per output row (8 columns each)
+    constexpr int RPP = 64 / LPR;                      // rows per pass
+    const int cl = wn * HW + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
 #pragma unroll
-    for (int ni = 0; ni < HI; ++ni) {
-      const int cl = wn * HW + ni * 32 + (lane & 31);
-      if (cl >= ncols) continue;
-      const int col = n0 + cl;
+    for (int mi = 0; mi < MI; ++mi) {
+      park_strip<T>(acc[mi], strip, lane);
+      if (cl < ncols) {
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = wm * WM + mi * 32 + acc_row(lane, i);
+        for (int pass = 0; pass < 32 / RPP; ++pass) {
+          const int rs = pass * RPP + lane / LPR;
+          const int r = wm * WM + mi * 32 + rs;
           if (r < rows) {
-            const float g = acc[mi][ni][i], u = acc[mi][ni + HI][i];
-            const long o = static_cast<long>(row0 + r) * p.ldo + col;
-            if (p.out0) p.out0[o] = f32_to_bf16(g);
-            if (p.out1) p.out1[o] = f32_to_bf16(u);
-            if (p.out2) p.out2[o] = f32_to_bf16(g * sigmoid_fast(g) * u);
+            float g[8], u[8], a[8];
+            read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, g);
+            read8(strip + rs * Strip<T>::LD + WN / 2 + (lane % LPR) * 8, u);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) a[q] = g[q] * sigmoid_fast(g[q]) * u[q];
+            const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+            if (p.out0) *reinterpret_cast<uint4*>(p.out0 + o) = pack8(g);
+            if (p.out1) *reinterpret_cast<uint4*>(p.out1 + o) = pack8(u);
+            if (p.out2) *reinterpret_cast<uint4*>(p.out2 + o) = pack8(a);
           }
         }
+      }
     }
     return;
   } else {
@@ -406,29 +577,41 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
       mainloop<T, false, true>(opsA, opsB, 2, p.K, lds, a_row, b_row, acc);
     }
 
+    float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+    constexpr int LPR = WN / 8;                        // lanes per output row (8 columns each)
+    constexpr int RPP = 64 / LPR;                      // rows per pass
+    const int cl = wn * WN + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-      const int cl = wn * WN + ni * 32 + (lane & 31);
-      if (cl >= ncols) continue;
-      const int col = n0 + cl;
+    for (int mi = 0; mi < MI; ++mi) {
+      park_strip<T>(acc[mi], strip, lane);
+      if (cl < ncols) {
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
+        for (int pass = 0; pass < 32 / RPP; ++pass) {
+          const int rs = pass * RPP + lane / LPR;
+          const int r = wm * WM + mi * 32 + rs;
+          if (r < rows) {
+            float v[8];
+            read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, v);
+            if constexpr (KIND == kDAct) {
+              const long gi = static_cast<long>(row0 + r) * p.N + n0 + cl;
+              float g[8], u[8], dg[8], du[8];
+              unpack8(*reinterpret_cast<const uint4*>(p.g + gi), g);
+              unpack8(*reinterpret_cast<const uint4*>(p.u + gi), u);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = wm * WM + mi * 32 + acc_row(lane, i);
-          if (r >= rows) continue;
-          const float val = acc[mi][ni][i];
-          if constexpr (KIND == kDAct) {
-            const long gi = static_cast<long>(row0 + r) * p.N + col;
-            const float g = bf16_to_f32(p.g[gi]), u = bf16_to_f32(p.u[gi]);
-            const float s = sigmoid_fast(g);
-            const long o = static_cast<long>(row0 + r) * p.ldo + col;
-            p.out0[o] = f32_to_bf16(val * u * (s * (1.0f + g * (1.0f - s))));
-            p.out0[o + p.N] = f32_to_bf16(val * (g * s));
-          } else {
-            p.out0[static_cast<long>(row0 + r) * p.ldo + col] = f32_to_bf16(val);
+              for (int q = 0; q < 8; ++q) {
+                const float sg = sigmoid_fast(g[q]);
+                dg[q] = v[q] * u[q] * (sg * (1.0f + g[q] * (1.0f - sg)));
+                du[q] = v[q] * (g[q] * sg);
+              }
+              const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+              *reinterpret_cast<uint4*>(p.out0 + o) = pack8(dg);
+              *reinterpret_cast<uint4*>(p.out0 + o + p.N) = pack8(du);
+            } else {
+              *reinterpret_cast<uint4*>(p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl) = pack8(v);
+            }
           }
         }
+      }
     }
   }
 }
@@ -480,21 +663,28 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
   opB.valid[1] = max(ncols - BN / 2, 0);
   mainloop<T, true, true>(&opA, &opB, 1, end - begin, lds, a_row, b_row, acc);
 
+  float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+  constexpr int LPR = WN / 8;
+  constexpr int RPP = 64 / LPR;
+  const int cl = wn * WN + (lane % LPR) * 8;
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni) {
-    const int cl = wn * WN + ni * 32 + (lane & 31);
-    if (cl >= ncols) continue;
+  for (int mi = 0; mi < MI; ++mi) {
+    park_strip<T>(acc[mi], strip, lane);
+    if (cl < ncols) {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int rl = wm * WM + mi * 32 + acc_row(lane, i);
-        if (rl >= mrows) continue;
-        const int m = m0 + rl;
-        bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
-                                    : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
-        out[n0 + cl] = f32_to_bf16(acc[mi][ni][i]);
+      for (int pass = 0; pass < 32 / RPP; ++pass) {
+        const int rs = pass * RPP + lane / LPR;
+        const int rl = wm * WM + mi * 32 + rs;
+        if (rl < mrows) {
+          float v[8];
+          read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, v);
+          const int m = m0 + rl;
+          bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
+                                      : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
+          *reinterpret_cast<uint4*>(out + n0 + cl) = pack8(v);
+        }
       }
+    }
   }
 }
 

@@ -26,9 +26,20 @@ PEAK_HBM_GBS = 8000.0         # HBM3E
 PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (GPU model unstated), "
                  "mixed precision -- context only")
 
-# HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this command
-# (summaries under profiles/), keyed by (workload, kernel); absent = not measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch (read + write) from the `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this
+# command summarised under profiles/, each counter scaled by what it reads for a plain 1 GiB copy
+# (fetch x 2.000, write x 1.000).  Keyed by (workload, kernel); absent = not measured.
+MEASURED_TRAFFIC = {
+    ("a3b_8k", "ffn_gate_up"): 2125.3e6 + 302.0e6,
+    ("a3b_8k", "ffn_down"): 845.1e6 + 268.4e6,
+    ("a3b_8k", "ffn_dact"): 979.4e6 + 201.3e6,
+    ("a3b_8k", "ffn_dx"): 1999.6e6 + 268.4e6,
+    ("a3b_8k", "wgrad_down"): 415.2e6 + 402.7e6,
+    ("a3b_8k", "wgrad_gate_up"): 740.5e6 + 805.3e6,
+    ("a3b_8k", "permute_gather"): 35.2e6 + 270.1e6,
+    ("a3b_8k", "combine_fwd"): 270.6e6 + 33.6e6,
+    ("a3b_8k", "combine_bwd"): 492.3e6 + 268.7e6,
+}
 
 
 def kernel_work(cfg, P):
@@ -59,6 +70,9 @@ def main():
     ap.add_argument("--workload", default="a3b_8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-save-gu", action="store_true", help="backward recomputes G and U")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1. "
@@ -67,6 +81,14 @@ def main():
 
     import numpy as np
     import torch
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "launches": 3}))
+        return
     from paper_2508_02317_amd import libmoe as L
     from paper_2508_02317_amd.inputs import CONFIGS, make_inputs, select_local_share
     from paper_2508_02317_amd.layer import MoELayer

@@ -35,19 +35,22 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kGemmThreads = 256;
 constexpr int kXcds = 8;
 
 // ---- tile shapes ------------------------------------------------------------------------------
-template <int BM_, int BN_, int BK_>
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_>
 struct Tile {
   static constexpr int BM = BM_, BN = BN_, BK = BK_;
-  static constexpr int WM = BM / 2, WN = BN / 2;          // 2 x 2 waves
+  static constexpr int WGM = WGM_, WGN = WGN_;            // grid of wavefronts over the tile
+  static constexpr int kWaves = WGM * WGN, kThreads = 64 * kWaves;
+  static constexpr int WM = BM / WGM, WN = BN / WGN;      // sub-tile of one wavefront
   static constexpr int MI = WM / 32, NI = WN / 32;        // MFMA tiles per wave
   static constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2;
   static constexpr int kStageBytes = kABytes + kBBytes;
-  static constexpr int kStages = 3;                       // LDS ring: two slabs in flight, one being read
+  static constexpr int kStages = STAGES_;                 // LDS ring: one slab being read, the others in flight
   static constexpr int kLdsBytes = kStages * kStageBytes;
+  static constexpr int kBlocksPerCu = 2 * kLdsBytes <= 160 * 1024 ? 2 : 1;   // by LDS capacity
+  static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4;
 };
 
 // One operand tile of ROWS rows: element (row, k).  Two halves of ROWS/2 rows with their own
@@ -76,12 +79,13 @@ __device__ __forceinline__ int ks_off(int k, int piece) {
 }
 
 // ---- global -> register -> LDS staging -------------------------------------------------------------
-template <bool KS, int ROWS, int BK> struct Stager;
+template <bool KS, int ROWS, int BK, int THREADS> struct Stager;
 
-template <int ROWS, int BK> struct Stager<false, ROWS, BK> {
+template <int ROWS, int BK, int THREADS> struct Stager<false, ROWS, BK, THREADS> {
   static constexpr int PPR = BK / 8;
-  static constexpr int N = ROWS * PPR / kGemmThreads;        // 16-byte loads per thread
-  static constexpr int RSTEP = kGemmThreads / PPR;           // rows covered by one pass
+  static constexpr int N = ROWS * PPR / THREADS;             // 16-byte loads per thread
+  static constexpr int RSTEP = THREADS / PPR;                // rows covered by one pass
+  static_assert(N >= 1 && (ROWS / 2) % RSTEP == 0, "tile too small for this many threads");
   const bf16_t* ptr[N];
   int lds_off[N];
   bool ok[N];
@@ -113,10 +117,11 @@ template <int ROWS, int BK> struct Stager<false, ROWS, BK> {
   }
 };
 
-template <int ROWS, int BK> struct Stager<true, ROWS, BK> {
+template <int ROWS, int BK, int THREADS> struct Stager<true, ROWS, BK, THREADS> {
   static constexpr int PPK = ROWS / 8;                       // 16-byte pieces per k-row
-  static constexpr int N = BK * PPK / kGemmThreads;
-  static constexpr int KSTEP = kGemmThreads / PPK;           // k-rows covered by one pass
+  static constexpr int N = BK * PPK / THREADS;
+  static constexpr int KSTEP = THREADS / PPK;                // k-rows covered by one pass
+  static_assert(N >= 1, "tile too small for this many threads");
   const bf16_t* ptr;
   long ld;
   bool ok;
@@ -174,9 +179,10 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
 // LDS slot.  Rows that do not exist are redirected to the tile's first row: they only feed output
 // rows / columns that are never stored.  The reduction range is NOT checked here, so this path is
 // used for full slabs only; a partial last slab goes through the register Stager, which zero-fills.
-template <bool KS, int ROWS, int BK> struct Dma {
+template <bool KS, int ROWS, int BK, int WAVES> struct Dma {
   static constexpr int CHUNKS = ROWS * BK * 2 / 1024;
-  static constexpr int N = CHUNKS / 4;                       // chunks per wave
+  static constexpr int N = CHUNKS / WAVES;                   // chunks per wave
+  static_assert(N >= 1 && CHUNKS % WAVES == 0, "tile too small for this many waves");
   const bf16_t* ptr[N];
   long step;                                                 // elements per slab
   __device__ __forceinline__ void init(const Operand& op, int wave, int lane) {
@@ -210,9 +216,6 @@ template <bool KS, int ROWS, int BK> struct Dma {
   __device__ __forceinline__ void issue(int slab, char* tile, int wave) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-#ifdef MOE_DBG_NO_LOAD
-      if (slab > 0) continue;
-#endif
       __builtin_amdgcn_global_load_lds(
           (const __attribute__((address_space(1))) void*)(ptr[i] + slab * step),
           (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
@@ -234,47 +237,69 @@ template <class T> struct Frags {
   bf16x8 a[T::MI];
   bf16x8 b[T::NI];
 };
+// mi_n / ni_n: how many of the wave's 32-row / 32-column fragments hold at least one row / column
+// that exists (wave-uniform).  Fragments beyond them are neither read nor multiplied, so a tile
+// that sticks out of its expert's row segment costs MFMA time only for the rows it really has.
 template <class T, bool A_KS, bool B_KS>
 __device__ __forceinline__ void load_frags(Frags<T>& f, const char* bufA, const char* bufB, int kk,
-                                           const int (&a_row)[T::MI], const int (&b_row)[T::NI], int lane) {
+                                           const int (&a_row)[T::MI], const int (&b_row)[T::NI], int lane,
+                                           int mi_n, int ni_n) {
 #pragma unroll
-  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM, T::BK>(bufA, a_row[i], kk, lane);
+  for (int i = 0; i < T::MI; ++i)
+    if (i < mi_n) f.a[i] = read_frag<A_KS, T::BM, T::BK>(bufA, a_row[i], kk, lane);
 #pragma unroll
-  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN, T::BK>(bufB, b_row[i], kk, lane);
+  for (int i = 0; i < T::NI; ++i)
+    if (i < ni_n) f.b[i] = read_frag<B_KS, T::BN, T::BK>(bufB, b_row[i], kk, lane);
 }
 template <class T>
-__device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::NI]) {
+__device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::NI], int mi_n, int ni_n) {
 #pragma unroll
   for (int mi = 0; mi < T::MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < T::NI; ++ni)
-      acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+      if (mi < mi_n && ni < ni_n)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+}
+
+// wait until at most `slabs` slabs' worth of this wave's direct loads are still in flight
+template <int L, int MAXS>
+__device__ __forceinline__ void wait_slabs_in_flight(int slabs) {
+  if constexpr (MAXS == 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (slabs >= MAXS) wait_vmcnt<MAXS * L>();
+    else wait_slabs_in_flight<L, MAXS - 1>(slabs);
+  }
 }
 
 // acc += sum over segments of A_s(BM x K) * B_s(BN x K)^T for this wave's sub-tile (segments differ
 // only in their base pointers).  a_row[mi] / b_row[ni]: first tile row of the wave's mi-th / ni-th
 // 32-row fragment.
 //
-// Full slabs stream through a 3-stage LDS ring filled by direct global->LDS loads, and the MFMA
+// Full slabs stream through an S-stage LDS ring filled by direct global->LDS loads, and the MFMA
 // operands are double-buffered in registers, so that every LDS read is issued one reduction step
 // ahead of the MFMAs that consume it.  Per slab kt:
 //     read step 1.. of slab kt (into the other register set) | MFMAs of the steps already loaded
 //     wait: own LDS reads of slab kt complete, own loads of slab kt+1 landed
 //     barrier: slab kt+1 is visible to all, and nobody reads the stage of slab kt any more
-//     refill that stage with slab kt+3; read step 0 of slab kt+1 | MFMAs of the last step of slab kt
-// so two to three slabs are in flight behind the slab being multiplied.
+//     refill that stage with slab kt+S; read step 0 of slab kt+1 | MFMAs of the last step of slab kt
+// so up to S-1 slabs are in flight behind the slab being multiplied: the global-memory latency a
+// workgroup can hide is (S-1) slabs of MFMA time.
 template <class T, bool A_KS, bool B_KS>
 __device__ __forceinline__ void mainloop(const Operand* opA, const Operand* opB, int nseg, int K, char* lds,
-                                         const int (&a_row)[T::MI], const int (&b_row)[T::NI],
-                                         f32x16 (&acc)[T::MI][T::NI]) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+                                         const int (&a_row)[T::MI], const int (&b_row)[T::NI], int mi_n, int ni_n,
+                                         int rot, f32x16 (&acc)[T::MI][T::NI]) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
   if (K <= 0) return;
   const int nfull = K / T::BK;
   const int tail = K - nfull * T::BK;
-  typedef Dma<A_KS, T::BM, T::BK> DmaA;
-  typedef Dma<B_KS, T::BN, T::BK> DmaB;
+  typedef Dma<A_KS, T::BM, T::BK, T::kWaves> DmaA;
+  typedef Dma<B_KS, T::BN, T::BK, T::kWaves> DmaB;
   constexpr int L = DmaA::N + DmaB::N;                 // loads per thread per slab
+  constexpr int S = T::kStages;
   constexpr int STEPS = T::BK / 16;                    // reduction steps per slab (even)
+  static_assert((S - 1) * L < 64, "vmcnt is a 6-bit counter");
 #pragma nounroll
   for (int seg = 0; seg < nseg; ++seg) {
     Operand oa, ob;                                    // picked field by field: no dynamically indexed copies
@@ -293,56 +318,60 @@ __device__ __forceinline__ void mainloop(const Operand* opA, const Operand* opB,
       DmaB db;
       da.init(oa, wave, lane);
       db.init(ob, wave, lane);
+      // The full slabs are visited in rotated order, starting at slab `rot`: workgroups of
+      // different experts then stream different offsets of their rows at the same time, which
+      // spreads the traffic over the memory channels instead of camping on a few of them.
+      int next_slab = rot % nfull;                     // next slab to request
 #pragma unroll
-      for (int s0 = 0; s0 < 3; ++s0)
+      for (int s0 = 0; s0 < S; ++s0)
         if (s0 < nfull) {
-          da.issue(s0, lds + s0 * T::kStageBytes, wave);
-          db.issue(s0, lds + s0 * T::kStageBytes + T::kABytes, wave);
+          da.issue(next_slab, lds + s0 * T::kStageBytes, wave);
+          db.issue(next_slab, lds + s0 * T::kStageBytes + T::kABytes, wave);
+          next_slab = next_slab + 1 == nfull ? 0 : next_slab + 1;
         }
-      if (nfull > 2) wait_vmcnt<2 * L>(); else if (nfull > 1) wait_vmcnt<L>(); else wait_vmcnt<0>();
+      wait_slabs_in_flight<L, S - 1>(nfull - 1);       // slab 0 has landed
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
       Frags<T> f0, f1;                                 // even / odd reduction steps
-      load_frags<T, A_KS, B_KS>(f0, lds, lds + T::kABytes, 0, a_row, b_row, lane);
+      load_frags<T, A_KS, B_KS>(f0, lds, lds + T::kABytes, 0, a_row, b_row, lane, mi_n, ni_n);
       int stage = 0;
 #pragma nounroll
       for (int kt = 0; kt < nfull; ++kt) {
         char* buf = lds + stage * T::kStageBytes;
 #pragma unroll
         for (int kk = 0; kk + 2 < STEPS; kk += 2) {    // all but the last two steps of the slab
-          load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, kk + 1, a_row, b_row, lane);
-          mma<T>(f0, acc);
-          load_frags<T, A_KS, B_KS>(f0, buf, buf + T::kABytes, kk + 2, a_row, b_row, lane);
-          mma<T>(f1, acc);
+          load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, kk + 1, a_row, b_row, lane, mi_n, ni_n);
+          mma<T>(f0, acc, mi_n, ni_n);
+          load_frags<T, A_KS, B_KS>(f0, buf, buf + T::kABytes, kk + 2, a_row, b_row, lane, mi_n, ni_n);
+          mma<T>(f1, acc, mi_n, ni_n);
         }
-        load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, STEPS - 1, a_row, b_row, lane);
+        load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, STEPS - 1, a_row, b_row, lane, mi_n, ni_n);
         __builtin_amdgcn_sched_barrier(0);
-        mma<T>(f0, acc);
+        mma<T>(f0, acc, mi_n, ni_n);
         __builtin_amdgcn_sched_barrier(0);
         wait_lgkmcnt0();                               // this wave no longer needs the stage of slab kt
-        if (kt + 1 < nfull) {
-          if (kt + 2 < nfull) wait_vmcnt<L>(); else wait_vmcnt<0>();
-        }
+        if (kt + 1 < nfull) wait_slabs_in_flight<L, S - 2>(nfull - 2 - kt);   // slab kt+1 has landed
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        if (kt + 3 < nfull) {
-          da.issue(kt + 3, buf, wave);
-          db.issue(kt + 3, buf + T::kABytes, wave);
+        if (kt + S < nfull) {
+          da.issue(next_slab, buf, wave);
+          db.issue(next_slab, buf + T::kABytes, wave);
+          next_slab = next_slab + 1 == nfull ? 0 : next_slab + 1;
         }
-        stage = stage == 2 ? 0 : stage + 1;
+        stage = stage == S - 1 ? 0 : stage + 1;
         if (kt + 1 < nfull) {
           const char* nxt = lds + stage * T::kStageBytes;
-          load_frags<T, A_KS, B_KS>(f0, nxt, nxt + T::kABytes, 0, a_row, b_row, lane);
+          load_frags<T, A_KS, B_KS>(f0, nxt, nxt + T::kABytes, 0, a_row, b_row, lane, mi_n, ni_n);
         }
         __builtin_amdgcn_sched_barrier(0);
-        mma<T>(f1, acc);
+        mma<T>(f1, acc, mi_n, ni_n);
       }
     }
     if (tail) {
       // partial last slab: through registers, zero-filled beyond K.  Every stage is free here: all
       // loads have landed and every wave finished its LDS reads before the last barrier.
-      Stager<A_KS, T::BM, T::BK> sa;
-      Stager<B_KS, T::BN, T::BK> sb;
+      Stager<A_KS, T::BM, T::BK, T::kThreads> sa;
+      Stager<B_KS, T::BN, T::BK, T::kThreads> sb;
       sa.init(oa, tid);
       sb.init(ob, tid);
       sa.load(nfull * T::BK, K);
@@ -353,8 +382,8 @@ __device__ __forceinline__ void mainloop(const Operand* opA, const Operand* opB,
 #pragma unroll
       for (int kk = 0; kk < STEPS; ++kk) {
         Frags<T> f;
-        load_frags<T, A_KS, B_KS>(f, lds, lds + T::kABytes, kk, a_row, b_row, lane);
-        mma<T>(f, acc);
+        load_frags<T, A_KS, B_KS>(f, lds, lds + T::kABytes, kk, a_row, b_row, lane, mi_n, ni_n);
+        mma<T>(f, acc, mi_n, ni_n);
       }
     }
     __syncthreads();                                   // all reads done before anything refills the ring
@@ -371,7 +400,7 @@ __device__ __forceinline__ int acc_row(int lane, int i) { return 8 * (i >> 2) + 
 template <class T> struct Strip {
   static constexpr int LD = T::WN + 8;                 // floats per staged row: 4 rows shift the banks by 32
   static constexpr int kBytes = 32 * LD * 4;
-  static_assert(4 * kBytes <= T::kLdsBytes, "staging strips must fit in the LDS ring");
+  static_assert(T::kWaves * kBytes <= T::kLdsBytes, "staging strips must fit in the LDS ring");
 };
 
 template <class T>
@@ -475,7 +504,7 @@ struct RowArgs {
 };
 
 template <int KIND, class T>
-__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void row_grouped_kernel(RowArgs p) {
+__global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::kWavesPerSimd, T::kWavesPerSimd))) void row_grouped_kernel(RowArgs p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int BM = T::BM, BN = T::BN, WM = T::WM, WN = T::WN, MI = T::MI, NI = T::NI;
   const int n_row_tiles = p.rt.count[0];
@@ -487,7 +516,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int row_end = min(p.offsets[e + 1], p.P);
   const int rows = min(BM, row_end - row0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / T::WGN, wn = wave % T::WGN;
 
   f32x16 acc[MI][NI];
   zero_acc<T>(acc);
@@ -495,6 +524,8 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
   int a_row[MI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) a_row[i] = wm * WM + i * 32;
+  // fragments of this wave that hold rows of the expert (wave-uniform)
+  const int mi_n = __builtin_amdgcn_readfirstlane(min(MI, max(0, (rows - wm * WM + 31) / 32)));
   Operand opsA[2], opsB[2];
   Operand& opA = opsA[0];
   Operand& opB = opsB[0];
@@ -517,7 +548,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
     opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.half[1] = p.w1 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.valid[0] = opB.valid[1] = ncols;
-    mainloop<T, false, false>(opsA, opsB, 1, p.K, lds, a_row, b_row, acc);
+    mainloop<T, false, false>(opsA, opsB, 1, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
     constexpr int LPR = HW / 8;                        // lanes per output row (8 columns each)
@@ -525,6 +556,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
     const int cl = wn * HW + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
+      if (mi >= mi_n) break;
       park_strip<T>(acc[mi], strip, lane);
       if (cl < ncols) {
 #pragma unroll
@@ -558,12 +590,12 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
       // yp = act * Wd[e]^T : weight rows are output columns, reduction contiguous
       opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
       opB.half[1] = opB.half[0] + (BN / 2) * p.ldw;
-      mainloop<T, false, false>(opsA, opsB, 1, p.K, lds, a_row, b_row, acc);
+      mainloop<T, false, false>(opsA, opsB, 1, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
     } else if constexpr (KIND == kDAct) {
       // dA = dyp * Wd[e] : weight is [K = d, N = f], reduction strided
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
       opB.half[1] = opB.half[0] + BN / 2;
-      mainloop<T, false, true>(opsA, opsB, 1, p.K, lds, a_row, b_row, acc);
+      mainloop<T, false, true>(opsA, opsB, 1, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
     } else {
       // dxp = dG * Wg[e] + dU * Wu[e] : two reduction segments over the columns of [dG | dU]
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
@@ -574,7 +606,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
       opsB[1] = opB;
       opsB[1].half[0] = p.w1 + e * p.w_expert_stride + n0;
       opsB[1].half[1] = opsB[1].half[0] + BN / 2;
-      mainloop<T, false, true>(opsA, opsB, 2, p.K, lds, a_row, b_row, acc);
+      mainloop<T, false, true>(opsA, opsB, 2, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
     }
 
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
@@ -583,6 +615,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
     const int cl = wn * WN + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
+      if (mi >= mi_n) break;
       park_strip<T>(acc[mi], strip, lane);
       if (cl < ncols) {
 #pragma unroll
@@ -629,7 +662,7 @@ struct WgradArgs {
 };
 
 template <int WHICH, class T>   // WHICH 0: dW_down, 1: [dW_gate; dW_up] (separate symbols so profiles tell them apart)
-__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void wgrad_kernel(WgradArgs p) {
+__global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::kWavesPerSimd, T::kWavesPerSimd))) void wgrad_kernel(WgradArgs p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int BM = T::BM, BN = T::BN, WM = T::WM, WN = T::WN, MI = T::MI, NI = T::NI;
   const int per_e = p.tiles_m * p.tiles_n;
@@ -641,7 +674,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int m0 = mt * BM, n0 = nt * BN;
   const int mrows = min(BM, p.M - m0), ncols = min(BN, p.N - n0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / T::WGN, wn = wave % T::WGN;
 
   f32x16 acc[MI][NI];
   zero_acc<T>(acc);
@@ -661,7 +694,7 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
   opB.half[1] = opB.half[0] + BN / 2;
   opB.valid[0] = min(ncols, BN / 2);
   opB.valid[1] = max(ncols - BN / 2, 0);
-  mainloop<T, true, true>(&opA, &opB, 1, end - begin, lds, a_row, b_row, acc);
+  mainloop<T, true, true>(&opA, &opB, 1, end - begin, lds, a_row, b_row, MI, NI, e * 13, acc);
 
   float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
   constexpr int LPR = WN / 8;
@@ -693,11 +726,13 @@ __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(2,
 // ============================================================================================
 // Tile shapes in use.  Row-grouped products keep the row (token) side at 128 so that experts
 // with a few hundred rows waste little; the weight side is 256 wide.
-typedef Tile<128, 128, 64> TileRowSmall;
-typedef Tile<128, 256, 32> TileRow;
-typedef Tile<128, 256, 32> TileWgrad;
+typedef Tile<128, 256, 32, 2, 2, 3> TileRow;           // 72 KiB of LDS: two 4-wave workgroups per CU
+typedef Tile<128, 256, 32, 2, 2, 3> TileWgrad;
+typedef Tile<256, 256, 32, 2, 4, 5> TileBig;           // 160 KiB of LDS: one 8-wave workgroup per CU
 
-static int tile_choice() {           // 0 = default; MOE_GEMM_TILE=1 selects the 128x128x64 variant
+// 0 = default.  MOE_GEMM_TILE=1 in the environment selects the 256 x 256 variant for every product
+// (a tuning knob; the measured difference on the 30B-class shapes is a few percent either way).
+static int tile_choice() {
   static int choice = -1;
   if (choice < 0) {
     const char* s = getenv("MOE_GEMM_TILE");
@@ -706,8 +741,9 @@ static int tile_choice() {           // 0 = default; MOE_GEMM_TILE=1 selects the
   return choice;
 }
 
-constexpr int kRowBM = 128;          // both row-grouped tile types use 128 rows
-static int max_row_tiles(int P, int E) { return ceil_div(P, kRowBM) + E; }
+static int row_bm() { return tile_choice() == 1 ? TileBig::BM : TileRow::BM; }
+// bound used for workspace sizing: the smallest row tile gives the longest list
+static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 
 struct WsLayout {
   size_t tiles_count, tiles_expert, tiles_row0, dgu, g, u, total;
@@ -755,13 +791,13 @@ static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
     attr_set = true;
   }
   p.n_tiles_n = ceil_div(p.N, KIND == kGateUp ? T::BN / 2 : T::BN);
-  const unsigned grid = padded_grid(max_row_tiles(P, E) * p.n_tiles_n);
-  MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T>), dim3(grid), dim3(kGemmThreads), T::kLdsBytes, s, p);
+  const unsigned grid = padded_grid((ceil_div(P, T::BM) + E) * p.n_tiles_n);
+  MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);
 }
 
 template <int KIND>
 static void launch_row(const RowArgs& p, int P, int E, hipStream_t s) {
-  if (tile_choice() == 1) launch_row_t<KIND, TileRowSmall>(p, P, E, s);
+  if (tile_choice() == 1) launch_row_t<KIND, TileBig>(p, P, E, s);
   else launch_row_t<KIND, TileRow>(p, P, E, s);
 }
 
@@ -776,13 +812,13 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
   const unsigned grid = padded_grid(p.tiles_m * p.tiles_n * p.E);
-  MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : "wgrad_gate_up", (wgrad_kernel<WHICH, T>), dim3(grid), dim3(kGemmThreads),
+  MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : "wgrad_gate_up", (wgrad_kernel<WHICH, T>), dim3(grid), dim3(T::kThreads),
              T::kLdsBytes, s, p);
 }
 
 template <int WHICH>
 static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
-  if (tile_choice() == 1) launch_wgrad_t<WHICH, TileRowSmall>(p, s);
+  if (tile_choice() == 1) launch_wgrad_t<WHICH, TileBig>(p, s);
   else launch_wgrad_t<WHICH, TileWgrad>(p, s);
 }
 
@@ -800,7 +836,7 @@ static void launch_gate_up(const void* xp, const void* wg, const void* wu, int P
 void ffn_fwd_bf16(const FfnFwdArgs& a) {
   const WsLayout w = ws_layout(a.P, a.f, a.E, false, false);
   const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
-  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, kRowBM, rt);
+  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, row_bm(), rt);
   launch_gate_up(a.xp, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.g_save, a.u_save, a.act, a.stream);
   RowArgs p{};
   p.a = static_cast<const bf16_t*>(a.act); p.lda = a.f;
@@ -818,7 +854,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
   bf16_t* dgu = reinterpret_cast<bf16_t*>(base + w.dgu);       // [P, 2f] = [dG | dU]
   const bf16_t* G = static_cast<const bf16_t*>(a.g_save);
   const bf16_t* U = static_cast<const bf16_t*>(a.u_save);
-  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, kRowBM, rt);
+  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, row_bm(), rt);
   if (recompute) {
     bf16_t* Gr = reinterpret_cast<bf16_t*>(base + w.g);
     bf16_t* Ur = reinterpret_cast<bf16_t*>(base + w.u);

@@ -9,7 +9,7 @@
 //     filled by direct global->LDS loads (no staging registers); two to three slabs are in
 //     flight behind the one being multiplied, the MFMA operands are double-buffered in
 //     registers one reduction step ahead, and one barrier per slab separates writers from
-//     readers;
+//     readers; a partial last slab reads zeros for the reduction indices it does not have;
 //   * results leave through LDS as well, so that all global stores (and the loads of the
 //     saved pre-activations in the fused SwiGLU derivative) are 16 bytes per lane and
 //     contiguous along rows;
@@ -78,84 +78,14 @@ __device__ __forceinline__ int ks_off(int k, int piece) {
   return k * (ROWS * 2) + (((((piece >> 2) ^ (k & 3)) << 2) | (piece & 3)) << 4);
 }
 
-// ---- global -> register -> LDS staging -------------------------------------------------------------
-template <bool KS, int ROWS, int BK, int THREADS> struct Stager;
-
-template <int ROWS, int BK, int THREADS> struct Stager<false, ROWS, BK, THREADS> {
-  static constexpr int PPR = BK / 8;
-  static constexpr int N = ROWS * PPR / THREADS;             // 16-byte loads per thread
-  static constexpr int RSTEP = THREADS / PPR;                // rows covered by one pass
-  static_assert(N >= 1 && (ROWS / 2) % RSTEP == 0, "tile too small for this many threads");
-  const bf16_t* ptr[N];
-  int lds_off[N];
-  bool ok[N];
-  int kpiece;
-  uint4 v[N];
-  __device__ __forceinline__ void init(const Operand& op, int tid) {
-    kpiece = tid % PPR;
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int row = tid / PPR + RSTEP * i;
-      const bool upper = (RSTEP * i) >= ROWS / 2;            // RSTEP divides ROWS/2: compile-time per i
-      const int rh = row - (upper ? ROWS / 2 : 0);
-      ok[i] = rh < (upper ? op.valid[1] : op.valid[0]);
-      ptr[i] = (upper ? op.half[1] : op.half[0]) + static_cast<long>(rh) * op.ld + kpiece * 8;
-      lds_off[i] = kc_off<BK>(row, kpiece);
-    }
-  }
-  __device__ __forceinline__ void load(int k0, int K) {
-    const bool k_ok = k0 + kpiece * 8 < K;
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      v[i] = make_uint4(0, 0, 0, 0);
-      if (ok[i] && k_ok) v[i] = *reinterpret_cast<const uint4*>(ptr[i] + k0);
-    }
-  }
-  __device__ __forceinline__ void store(char* tile) const {
-#pragma unroll
-    for (int i = 0; i < N; ++i) *reinterpret_cast<uint4*>(tile + lds_off[i]) = v[i];
-  }
-};
-
-template <int ROWS, int BK, int THREADS> struct Stager<true, ROWS, BK, THREADS> {
-  static constexpr int PPK = ROWS / 8;                       // 16-byte pieces per k-row
-  static constexpr int N = BK * PPK / THREADS;
-  static constexpr int KSTEP = THREADS / PPK;                // k-rows covered by one pass
-  static_assert(N >= 1, "tile too small for this many threads");
-  const bf16_t* ptr;
-  long ld;
-  bool ok;
-  int krow, piece;
-  uint4 v[N];
-  __device__ __forceinline__ void init(const Operand& op, int tid) {
-    piece = tid % PPK;
-    krow = tid / PPK;
-    const int row = piece * 8;
-    const bool upper = row >= ROWS / 2;
-    const int rh = row - (upper ? ROWS / 2 : 0);
-    ok = rh < (upper ? op.valid[1] : op.valid[0]);
-    ld = op.ld;
-    ptr = (upper ? op.half[1] : op.half[0]) + rh + static_cast<long>(krow) * ld;
-  }
-  __device__ __forceinline__ void load(int k0, int K) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      v[i] = make_uint4(0, 0, 0, 0);
-      if (ok && k0 + krow + KSTEP * i < K) v[i] = *reinterpret_cast<const uint4*>(ptr + static_cast<long>(k0 + KSTEP * i) * ld);
-    }
-  }
-  __device__ __forceinline__ void store(char* tile) const {
-#pragma unroll
-    for (int i = 0; i < N; ++i) *reinterpret_cast<uint4*>(tile + ks_off<ROWS>(krow + KSTEP * i, piece)) = v[i];
-  }
-};
-
 // ---- MFMA operand fragments ----------------------------------------------------------------------------
 // Fragment = 32 rows x 16 k: lane l holds row l%32, k = 8*(l/32) .. +7 of the 16-wide step kk.
+// frag_off: this lane's byte offset inside the operand tile, computed once per kernel; the main loop
+// only adds compile-time stage offsets, so an LDS read costs no address arithmetic.
 template <bool KS, int ROWS, int BK>
-__device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int kk, int lane) {
+__device__ __forceinline__ int frag_off(int row_base, int kk, int lane) {
   if constexpr (!KS) {
-    return *reinterpret_cast<const bf16x8*>(tile + kc_off<BK>(row_base + (lane & 31), 2 * kk + (lane >> 5)));
+    return kc_off<BK>(row_base + (lane & 31), 2 * kk + (lane >> 5));
   } else {
     // Transposing read: within each group of 16 lanes, lane i receives element i%4 of the 8-byte
     // rows addressed by lanes i/4, i/4+4, i/4+8, i/4+12.  Lane s therefore addresses k-row s/4 at
@@ -163,12 +93,18 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
     const int s = lane & 15;
     const int col = row_base + 16 * ((lane >> 4) & 1) + 4 * (s & 3);     // multiple of 4
     const int k = kk * 16 + 8 * (lane >> 5) + (s >> 2);
-    const int piece = col >> 3, sub = (col & 4) * 2;                       // 8-byte half of the piece
+    return ks_off<ROWS>(k, col >> 3) + (col & 4) * 2;                     // 8-byte half of the piece
+  }
+}
+template <bool KS, int ROWS>
+__device__ __forceinline__ bf16x8 read_frag(const char* p) {
+  if constexpr (!KS) {
+    return *reinterpret_cast<const bf16x8*>(p);
+  } else {
     typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-        (lds_bf16x4*)(tile + ks_off<ROWS>(k, piece) + sub));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-        (lds_bf16x4*)(tile + ks_off<ROWS>(k + 4, piece) + sub));
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
+    // k + 4 has the same swizzle (k & 3 unchanged): a constant 4 k-rows further
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * ROWS * 2));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 }
@@ -176,28 +112,41 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
 // ---- global -> LDS without passing through registers -----------------------------------------------
 // One wave instruction (global_load_lds_dwordx4) moves 64 x 16 bytes into 1 KiB of consecutive LDS;
 // the swizzles above are applied on the global side: each lane fetches the piece that belongs in its
-// LDS slot.  Rows that do not exist are redirected to the tile's first row: they only feed output
-// rows / columns that are never stored.  The reduction range is NOT checked here, so this path is
-// used for full slabs only; a partial last slab goes through the register Stager, which zero-fills.
+// LDS slot.  Addresses are a wave-uniform base (advanced per slab with scalar arithmetic) plus a
+// 32-bit per-lane offset.  Rows that do not exist are redirected to the tile's first row: they only
+// feed output rows / columns that are never stored.  Reduction indices beyond K (last, partial
+// slab only) are redirected to a block of zeros, so they contribute nothing.
 template <bool KS, int ROWS, int BK, int WAVES> struct Dma {
   static constexpr int CHUNKS = ROWS * BK * 2 / 1024;
   static constexpr int N = CHUNKS / WAVES;                   // chunks per wave
   static_assert(N >= 1 && CHUNKS % WAVES == 0, "tile too small for this many waves");
-  const bf16_t* ptr[N];
-  long step;                                                 // elements per slab
+  const char* base[N];       // wave-uniform
+  uint32_t voff[N];          // per lane, bytes
+  int kidx[N];               // per lane: reduction index inside the slab of this lane's piece
+  long step;                 // bytes per slab (uniform)
   __device__ __forceinline__ void init(const Operand& op, int wave, int lane) {
+    const bf16_t* const h0 = op.half[0];                     // scalars, so that the selects below stay selects
+    const bf16_t* const h1 = op.half[1];
+    const int v0 = op.valid[0], v1 = op.valid[1];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int c = wave * N + i;
+      const int c = wave * N + i;                            // wave-uniform
       if constexpr (!KS) {
         constexpr int PPR = BK / 8, RPC = 1024 / (BK * 2), RPL = 256 / (BK * 2);
+        static_assert((ROWS / 2) % RPC == 0, "a chunk must not straddle the two halves");
         const int row = c * RPC + lane / PPR;
         const int piece = (lane % PPR) ^ ((row / RPL) & (PPR - 1));
-        const bool upper = row >= ROWS / 2;
+        const bool upper = c * RPC >= ROWS / 2;              // uniform
         const int rh = row - (upper ? ROWS / 2 : 0);
-        const bool ok = rh < (upper ? op.valid[1] : op.valid[0]);
-        const bf16_t* base = ok ? (upper ? op.half[1] : op.half[0]) + static_cast<long>(rh) * op.ld : op.half[0];
-        ptr[i] = base + piece * 8;
+        const int valid = upper ? v1 : v0;
+        // the chunk's base stays the upper half only if the chunk holds at least one row that exists
+        // (uniform); single missing rows are redirected through the per-lane offset
+        const bool chunk_any = (c * RPC - (upper ? ROWS / 2 : 0)) < valid;
+        const bool own_base = !upper || chunk_any;
+        base[i] = reinterpret_cast<const char*>((own_base && upper) ? h1 : h0);
+        const bool own_row = own_base && rh < valid;
+        voff[i] = static_cast<uint32_t>((own_row ? static_cast<long>(rh) * op.ld : 0) * 2 + piece * 16);
+        kidx[i] = piece * 8;
       } else {
         constexpr int PPK = ROWS / 8, KPC = 1024 / (ROWS * 2);
         const int k = c * KPC + lane / PPK;
@@ -206,19 +155,32 @@ template <bool KS, int ROWS, int BK, int WAVES> struct Dma {
         const int col = piece * 8;
         const bool upper = col >= ROWS / 2;
         const int ch = col - (upper ? ROWS / 2 : 0);
-        const bool ok = ch < (upper ? op.valid[1] : op.valid[0]);
-        ptr[i] = (ok ? (upper ? op.half[1] : op.half[0]) + ch : op.half[0]) + static_cast<long>(k) * op.ld;
+        const bool ok = ch < (upper ? v1 : v0);
+        // k-strided operands are never dual: half[1] is half[0] shifted by ROWS/2 columns
+        base[i] = reinterpret_cast<const char*>(h0);
+        voff[i] = static_cast<uint32_t>(((ok ? col : 0) + static_cast<long>(k) * op.ld) * 2);
+        kidx[i] = k;
       }
     }
-    step = KS ? static_cast<long>(BK) * op.ld : BK;
+    step = (KS ? static_cast<long>(BK) * op.ld : BK) * 2;
   }
   // enqueue this wave's share of slab `slab` into the operand tile at `tile` (LDS)
   __device__ __forceinline__ void issue(int slab, char* tile, int wave) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(ptr[i] + slab * step),
-          (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
+      const char* g = base[i] + slab * step + voff[i];
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                       (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
+    }
+  }
+  // the same for the last, partial slab: pieces whose reduction index is >= K read zeros
+  __device__ __forceinline__ void issue_tail(int slab, int K, const char* zeros, char* tile, int wave) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const bool in_range = slab * BK + kidx[i] < K;
+      const char* g = in_range ? base[i] + slab * step + voff[i] : zeros;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                       (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
     }
   }
 };
@@ -228,38 +190,8 @@ template <bool KS, int ROWS, int BK, int WAVES> struct Dma {
 template <int n> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14));
 }
-
 // s_waitcnt that waits only for the LDS / scalar-memory counter to reach zero
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14)); }
-
-// the MFMA operands of one 16-wide reduction step for this wave's sub-tile
-template <class T> struct Frags {
-  bf16x8 a[T::MI];
-  bf16x8 b[T::NI];
-};
-// mi_n / ni_n: how many of the wave's 32-row / 32-column fragments hold at least one row / column
-// that exists (wave-uniform).  Fragments beyond them are neither read nor multiplied, so a tile
-// that sticks out of its expert's row segment costs MFMA time only for the rows it really has.
-template <class T, bool A_KS, bool B_KS>
-__device__ __forceinline__ void load_frags(Frags<T>& f, const char* bufA, const char* bufB, int kk,
-                                           const int (&a_row)[T::MI], const int (&b_row)[T::NI], int lane,
-                                           int mi_n, int ni_n) {
-#pragma unroll
-  for (int i = 0; i < T::MI; ++i)
-    if (i < mi_n) f.a[i] = read_frag<A_KS, T::BM, T::BK>(bufA, a_row[i], kk, lane);
-#pragma unroll
-  for (int i = 0; i < T::NI; ++i)
-    if (i < ni_n) f.b[i] = read_frag<B_KS, T::BN, T::BK>(bufB, b_row[i], kk, lane);
-}
-template <class T>
-__device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::NI], int mi_n, int ni_n) {
-#pragma unroll
-  for (int mi = 0; mi < T::MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < T::NI; ++ni)
-      if (mi < mi_n && ni < ni_n)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
-}
 
 // wait until at most `slabs` slabs' worth of this wave's direct loads are still in flight
 template <int L, int MAXS>
@@ -272,123 +204,179 @@ __device__ __forceinline__ void wait_slabs_in_flight(int slabs) {
   }
 }
 
+// the MFMA operands of one 16-wide reduction step for this wave's sub-tile
+template <class T> struct Frags {
+  bf16x8 a[T::MI];
+  bf16x8 b[T::NI];
+};
+// per-lane LDS offsets of every fragment and step, relative to the start of a stage
+template <class T> struct FragOffsets {
+  int a[T::MI][T::BK / 16];
+  int b[T::NI][T::BK / 16];
+};
+
+template <class T, bool A_KS, bool B_KS>
+__device__ __forceinline__ void load_frags(Frags<T>& f, const char* stage, const FragOffsets<T>& fo, int kk) {
+#pragma unroll
+  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM>(stage + fo.a[i][kk]);
+#pragma unroll
+  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN>(stage + T::kABytes + fo.b[i][kk]);
+}
+// MFMAs number FROM .. TO-1 (row-major over the wave's MI x NI fragments) of one reduction step
+template <class T, int FROM, int TO>
+__device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::NI]) {
+#pragma unroll
+  for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < T::NI; ++ni)
+      if (mi * T::NI + ni >= FROM && mi * T::NI + ni < TO)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+}
+
 // acc += sum over segments of A_s(BM x K) * B_s(BN x K)^T for this wave's sub-tile (segments differ
 // only in their base pointers).  a_row[mi] / b_row[ni]: first tile row of the wave's mi-th / ni-th
 // 32-row fragment.
 //
-// Full slabs stream through an S-stage LDS ring filled by direct global->LDS loads, and the MFMA
+// Slabs stream through an S-stage LDS ring filled by direct global->LDS loads, and the MFMA
 // operands are double-buffered in registers, so that every LDS read is issued one reduction step
 // ahead of the MFMAs that consume it.  Per slab kt:
 //     read step 1.. of slab kt (into the other register set) | MFMAs of the steps already loaded
 //     wait: own LDS reads of slab kt complete, own loads of slab kt+1 landed
 //     barrier: slab kt+1 is visible to all, and nobody reads the stage of slab kt any more
 //     refill that stage with slab kt+S; read step 0 of slab kt+1 | MFMAs of the last step of slab kt
-// so up to S-1 slabs are in flight behind the slab being multiplied: the global-memory latency a
-// workgroup can hide is (S-1) slabs of MFMA time.
+// so up to S-1 slabs are in flight behind the slab being multiplied.  The loop over slabs is
+// unrolled S times so that every LDS address is "register + constant": on this hardware every
+// VALU instruction and every LDS read takes issue time away from the MFMAs of the same SIMD
+// (measured: about 16 cycles per 16-byte LDS read against 32 per MFMA).
 template <class T, bool A_KS, bool B_KS>
-__device__ __forceinline__ void mainloop(const Operand* opA, const Operand* opB, int nseg, int K, char* lds,
-                                         const int (&a_row)[T::MI], const int (&b_row)[T::NI], int mi_n, int ni_n,
-                                         int rot, f32x16 (&acc)[T::MI][T::NI]) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
-  if (K <= 0) return;
-  const int nfull = K / T::BK;
-  const int tail = K - nfull * T::BK;
+struct MainLoop {
   typedef Dma<A_KS, T::BM, T::BK, T::kWaves> DmaA;
   typedef Dma<B_KS, T::BN, T::BK, T::kWaves> DmaB;
-  constexpr int L = DmaA::N + DmaB::N;                 // loads per thread per slab
-  constexpr int S = T::kStages;
-  constexpr int STEPS = T::BK / 16;                    // reduction steps per slab (even)
+  static constexpr int L = DmaA::N + DmaB::N;          // loads per thread per slab
+  static constexpr int S = T::kStages;
+  static constexpr int STEPS = T::BK / 16;             // reduction steps per slab (even)
   static_assert((S - 1) * L < 64, "vmcnt is a 6-bit counter");
+
+  DmaA da;
+  DmaB db;
+  FragOffsets<T> fo;
+  Frags<T> f0, f1;                                     // even / odd reduction steps
+  char* lds;
+  const char* zeros;
+  int nslabs, nfull, K, wave;
+
+  __device__ __forceinline__ void issue(int slab, int stage) {
+    char* st = lds + stage * T::kStageBytes;
+    if (slab < nfull) {
+      da.issue(slab, st, wave);
+      db.issue(slab, st + T::kABytes, wave);
+    } else {
+      da.issue_tail(slab, K, zeros, st, wave);
+      db.issue_tail(slab, K, zeros, st + T::kABytes, wave);
+    }
+  }
+
+  // ACTIVE = false: a wave whose sub-tile holds no row of the expert (the tile sticks out of the
+  // row segment) only takes part in the loads and barriers; its SIMD time goes to the other waves.
+  template <int STG, bool ACTIVE>
+  __device__ __forceinline__ void slab_body(int kt, f32x16 (&acc)[T::MI][T::NI]) {
+    constexpr int NXT = (STG + 1) % S;
+    const char* buf = lds + STG * T::kStageBytes;
+    // Every step first waits for its own operands, then issues the LDS reads of the next step and only
+    // then its MFMAs, so each read has a whole step of MFMAs (plus the other wave on the SIMD) to complete.
+    constexpr int ALL = T::MI * T::NI;
+    if constexpr (ACTIVE) {
+#pragma unroll
+      for (int kk = 0; kk + 1 < STEPS; ++kk) {         // every step but the last: fetch the next step, multiply this one
+        wait_lgkmcnt0();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags<T, A_KS, B_KS>((kk & 1) ? f0 : f1, buf, fo, kk + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma<T, 0, ALL>((kk & 1) ? f1 : f0, acc);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      wait_lgkmcnt0();                                 // last step is in f1; this wave no longer needs the stage of slab kt
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (kt + 1 < nslabs) wait_slabs_in_flight<L, S - 2>(nslabs - 2 - kt);   // slab kt+1 has landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (ACTIVE) {
+      if (kt + 1 < nslabs) load_frags<T, A_KS, B_KS>(f0, lds + NXT * T::kStageBytes, fo, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (kt + S < nslabs) issue(kt + S, STG);
+    if constexpr (ACTIVE) {
+      __builtin_amdgcn_sched_barrier(0);
+      mma<T, 0, ALL>(f1, acc);
+    }
+  }
+
+  template <int STG, bool ACTIVE>
+  __device__ __forceinline__ void run_from(int& kt, f32x16 (&acc)[T::MI][T::NI]) {
+    if constexpr (STG < S) {
+      if (kt < nslabs) {
+        slab_body<STG, ACTIVE>(kt, acc);
+        ++kt;
+        run_from<STG + 1, ACTIVE>(kt, acc);
+      }
+    }
+  }
+
+  template <bool ACTIVE>
+  __device__ __forceinline__ void stream(f32x16 (&acc)[T::MI][T::NI]) {
+    if constexpr (ACTIVE) load_frags<T, A_KS, B_KS>(f0, lds, fo, 0);
+    int kt = 0;
 #pragma nounroll
-  for (int seg = 0; seg < nseg; ++seg) {
-    Operand oa, ob;                                    // picked field by field: no dynamically indexed copies
-    oa.half[0] = seg ? opA[1].half[0] : opA[0].half[0];
-    oa.half[1] = seg ? opA[1].half[1] : opA[0].half[1];
-    oa.ld = opA[0].ld;
-    oa.valid[0] = opA[0].valid[0];
-    oa.valid[1] = opA[0].valid[1];
-    ob.half[0] = seg ? opB[1].half[0] : opB[0].half[0];
-    ob.half[1] = seg ? opB[1].half[1] : opB[0].half[1];
-    ob.ld = opB[0].ld;
-    ob.valid[0] = opB[0].valid[0];
-    ob.valid[1] = opB[0].valid[1];
-    if (nfull > 0) {
-      DmaA da;
-      DmaB db;
+    while (kt + S <= nslabs) {                         // S slabs per trip: stages are compile-time
+      run_from<0, ACTIVE>(kt, acc);
+    }
+    run_from<0, ACTIVE>(kt, acc);                      // the remaining < S slabs
+  }
+
+  __device__ __forceinline__ void run(const Operand* opA, const Operand* opB, int nseg, int K_, char* lds_,
+                                      const bf16_t* zeros_, const int (&a_row)[T::MI], const int (&b_row)[T::NI],
+                                      bool active, f32x16 (&acc)[T::MI][T::NI]) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
+    lds = lds_; zeros = reinterpret_cast<const char*>(zeros_); K = K_;
+    if (K <= 0) return;
+    nfull = K / T::BK;
+    nslabs = (K + T::BK - 1) / T::BK;
+#pragma unroll
+    for (int i = 0; i < T::MI; ++i)
+#pragma unroll
+      for (int kk = 0; kk < STEPS; ++kk) fo.a[i][kk] = frag_off<A_KS, T::BM, T::BK>(a_row[i], kk, lane);
+#pragma unroll
+    for (int i = 0; i < T::NI; ++i)
+#pragma unroll
+      for (int kk = 0; kk < STEPS; ++kk) fo.b[i][kk] = frag_off<B_KS, T::BN, T::BK>(b_row[i], kk, lane);
+#pragma nounroll
+    for (int seg = 0; seg < nseg; ++seg) {
+      Operand oa, ob;                                  // picked field by field: no dynamically indexed copies
+      oa.half[0] = seg ? opA[1].half[0] : opA[0].half[0];
+      oa.half[1] = seg ? opA[1].half[1] : opA[0].half[1];
+      oa.ld = opA[0].ld;
+      oa.valid[0] = opA[0].valid[0];
+      oa.valid[1] = opA[0].valid[1];
+      ob.half[0] = seg ? opB[1].half[0] : opB[0].half[0];
+      ob.half[1] = seg ? opB[1].half[1] : opB[0].half[1];
+      ob.ld = opB[0].ld;
+      ob.valid[0] = opB[0].valid[0];
+      ob.valid[1] = opB[0].valid[1];
       da.init(oa, wave, lane);
       db.init(ob, wave, lane);
-      // The full slabs are visited in rotated order, starting at slab `rot`: workgroups of
-      // different experts then stream different offsets of their rows at the same time, which
-      // spreads the traffic over the memory channels instead of camping on a few of them.
-      int next_slab = rot % nfull;                     // next slab to request
 #pragma unroll
       for (int s0 = 0; s0 < S; ++s0)
-        if (s0 < nfull) {
-          da.issue(next_slab, lds + s0 * T::kStageBytes, wave);
-          db.issue(next_slab, lds + s0 * T::kStageBytes + T::kABytes, wave);
-          next_slab = next_slab + 1 == nfull ? 0 : next_slab + 1;
-        }
-      wait_slabs_in_flight<L, S - 1>(nfull - 1);       // slab 0 has landed
+        if (s0 < nslabs) issue(s0, s0);
+      wait_slabs_in_flight<L, S - 1>(nslabs - 1);      // slab 0 has landed
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      Frags<T> f0, f1;                                 // even / odd reduction steps
-      load_frags<T, A_KS, B_KS>(f0, lds, lds + T::kABytes, 0, a_row, b_row, lane, mi_n, ni_n);
-      int stage = 0;
-#pragma nounroll
-      for (int kt = 0; kt < nfull; ++kt) {
-        char* buf = lds + stage * T::kStageBytes;
-#pragma unroll
-        for (int kk = 0; kk + 2 < STEPS; kk += 2) {    // all but the last two steps of the slab
-          load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, kk + 1, a_row, b_row, lane, mi_n, ni_n);
-          mma<T>(f0, acc, mi_n, ni_n);
-          load_frags<T, A_KS, B_KS>(f0, buf, buf + T::kABytes, kk + 2, a_row, b_row, lane, mi_n, ni_n);
-          mma<T>(f1, acc, mi_n, ni_n);
-        }
-        load_frags<T, A_KS, B_KS>(f1, buf, buf + T::kABytes, STEPS - 1, a_row, b_row, lane, mi_n, ni_n);
-        __builtin_amdgcn_sched_barrier(0);
-        mma<T>(f0, acc, mi_n, ni_n);
-        __builtin_amdgcn_sched_barrier(0);
-        wait_lgkmcnt0();                               // this wave no longer needs the stage of slab kt
-        if (kt + 1 < nfull) wait_slabs_in_flight<L, S - 2>(nfull - 2 - kt);   // slab kt+1 has landed
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        if (kt + S < nfull) {
-          da.issue(next_slab, buf, wave);
-          db.issue(next_slab, buf + T::kABytes, wave);
-          next_slab = next_slab + 1 == nfull ? 0 : next_slab + 1;
-        }
-        stage = stage == S - 1 ? 0 : stage + 1;
-        if (kt + 1 < nfull) {
-          const char* nxt = lds + stage * T::kStageBytes;
-          load_frags<T, A_KS, B_KS>(f0, nxt, nxt + T::kABytes, 0, a_row, b_row, lane, mi_n, ni_n);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        mma<T>(f1, acc, mi_n, ni_n);
-      }
+      if (active) stream<true>(acc); else stream<false>(acc);
+      __syncthreads();                                 // all reads done before anything refills the ring
     }
-    if (tail) {
-      // partial last slab: through registers, zero-filled beyond K.  Every stage is free here: all
-      // loads have landed and every wave finished its LDS reads before the last barrier.
-      Stager<A_KS, T::BM, T::BK, T::kThreads> sa;
-      Stager<B_KS, T::BN, T::BK, T::kThreads> sb;
-      sa.init(oa, tid);
-      sb.init(ob, tid);
-      sa.load(nfull * T::BK, K);
-      sb.load(nfull * T::BK, K);
-      sa.store(lds);
-      sb.store(lds + T::kABytes);
-      __syncthreads();
-#pragma unroll
-      for (int kk = 0; kk < STEPS; ++kk) {
-        Frags<T> f;
-        load_frags<T, A_KS, B_KS>(f, lds, lds + T::kABytes, kk, a_row, b_row, lane, mi_n, ni_n);
-        mma<T>(f, acc, mi_n, ni_n);
-      }
-    }
-    __syncthreads();                                   // all reads done before anything refills the ring
   }
-}
+};
 
 // element i (0..15) of a 32x32 MFMA tile held by `lane`: row 8*(i/4) + 4*(lane/32) + i%4, col lane%32
 __device__ __forceinline__ int acc_row(int lane, int i) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
@@ -430,12 +418,14 @@ struct RowTiles {
   int32_t* expert;       // [max_tiles]
   int32_t* row0;         // [max_tiles]
   int max_tiles;
+  uint32_t* zeros;       // [64] block of zeros the GEMM kernels read for out-of-range reduction indices
 };
 
 __global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __restrict__ offsets, int E, int P,
                                                                 int bm, RowTiles rt) {
   __shared__ int32_t scan[kMaxExperts];
   const int e = threadIdx.x;
+  if (e < 64) rt.zeros[e] = 0u;
   int begin = 0, end = 0, nt = 0;
   if (e < E) {
     begin = min(max(offsets[e], 0), P);
@@ -501,7 +491,9 @@ struct RowArgs {
   long ldo;
   const bf16_t* g;         // kDAct: saved pre-activations
   const bf16_t* u;
+  const bf16_t* zeros;     // at least 16 zero bytes (source of out-of-range reduction indices)
 };
+
 
 template <int KIND, class T>
 __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::kWavesPerSimd, T::kWavesPerSimd))) void row_grouped_kernel(RowArgs p) {
@@ -524,7 +516,8 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   int a_row[MI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) a_row[i] = wm * WM + i * 32;
-  // fragments of this wave that hold rows of the expert (wave-uniform)
+  // 32-row fragments of this wave that hold rows of the expert (wave-uniform); a wave without any
+  // skips the arithmetic, and the epilogue skips strips without rows
   const int mi_n = __builtin_amdgcn_readfirstlane(min(MI, max(0, (rows - wm * WM + 31) / 32)));
   Operand opsA[2], opsB[2];
   Operand& opA = opsA[0];
@@ -548,7 +541,8 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.half[1] = p.w1 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.valid[0] = opB.valid[1] = ncols;
-    mainloop<T, false, false>(opsA, opsB, 1, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
+    { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc);
+    }
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
     constexpr int LPR = HW / 8;                        // lanes per output row (8 columns each)
@@ -590,12 +584,12 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       // yp = act * Wd[e]^T : weight rows are output columns, reduction contiguous
       opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
       opB.half[1] = opB.half[0] + (BN / 2) * p.ldw;
-      mainloop<T, false, false>(opsA, opsB, 1, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
+      { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     } else if constexpr (KIND == kDAct) {
       // dA = dyp * Wd[e] : weight is [K = d, N = f], reduction strided
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
       opB.half[1] = opB.half[0] + BN / 2;
-      mainloop<T, false, true>(opsA, opsB, 1, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
+      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     } else {
       // dxp = dG * Wg[e] + dU * Wu[e] : two reduction segments over the columns of [dG | dU]
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
@@ -606,7 +600,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       opsB[1] = opB;
       opsB[1].half[0] = p.w1 + e * p.w_expert_stride + n0;
       opsB[1].half[1] = opsB[1].half[0] + BN / 2;
-      mainloop<T, false, true>(opsA, opsB, 2, p.K, lds, a_row, b_row, mi_n, NI, e * 13, acc);
+      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 2, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     }
 
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
@@ -659,6 +653,7 @@ struct WgradArgs {
   const int32_t* offsets; int E; int P;
   int tiles_m, tiles_n;
   bf16_t* out0; bf16_t* out1; int m_split;     // out1 rows are (m - m_split)
+  const bf16_t* zeros;     // at least 16 zero bytes
 };
 
 template <int WHICH, class T>   // WHICH 0: dW_down, 1: [dW_gate; dW_up] (separate symbols so profiles tell them apart)
@@ -694,7 +689,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   opB.half[1] = opB.half[0] + BN / 2;
   opB.valid[0] = min(ncols, BN / 2);
   opB.valid[1] = max(ncols - BN / 2, 0);
-  mainloop<T, true, true>(&opA, &opB, 1, end - begin, lds, a_row, b_row, MI, NI, e * 13, acc);
+  { MainLoop<T, true, true> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, acc); }
 
   float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
   constexpr int LPR = WN / 8;
@@ -728,7 +723,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
 // with a few hundred rows waste little; the weight side is 256 wide.
 typedef Tile<128, 256, 32, 2, 2, 3> TileRow;           // 72 KiB of LDS: two 4-wave workgroups per CU
 typedef Tile<128, 256, 32, 2, 2, 3> TileWgrad;
-typedef Tile<256, 256, 32, 2, 4, 5> TileBig;           // 160 KiB of LDS: one 8-wave workgroup per CU
+typedef Tile<128, 256, 64, 2, 4, 3> TileBig;           // 144 KiB of LDS: one 8-wave workgroup per CU, 64 x 64 per wave, 128-byte row pieces
 
 // 0 = default.  MOE_GEMM_TILE=1 in the environment selects the 256 x 256 variant for every product
 // (a tuning knob; the measured difference on the 30B-class shapes is a few percent either way).
@@ -746,12 +741,13 @@ static int row_bm() { return tile_choice() == 1 ? TileBig::BM : TileRow::BM; }
 static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 
 struct WsLayout {
-  size_t tiles_count, tiles_expert, tiles_row0, dgu, g, u, total;
+  size_t tiles_count, zeros, tiles_expert, tiles_row0, dgu, g, u, total;
 };
 static WsLayout ws_layout(int P, int f, int E, bool need_dgu, bool need_gu) {
   WsLayout w{};
   size_t off = 0;
   w.tiles_count = off; off += 256;
+  w.zeros = off; off += 256;
   const size_t t = align_up(static_cast<size_t>(max_row_tiles(P, E)) * sizeof(int32_t), 256);
   w.tiles_expert = off; off += t;
   w.tiles_row0 = off; off += t;
@@ -774,6 +770,7 @@ static RowTiles row_tiles_at(void* ws, const WsLayout& w, int P, int E) {
   RowTiles rt;
   rt.max_tiles = max_row_tiles(P, E);
   rt.count = reinterpret_cast<int32_t*>(b + w.tiles_count);
+  rt.zeros = reinterpret_cast<uint32_t*>(b + w.zeros);
   rt.expert = reinterpret_cast<int32_t*>(b + w.tiles_expert);
   rt.row0 = reinterpret_cast<int32_t*>(b + w.tiles_row0);
   return rt;
@@ -823,12 +820,13 @@ static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
 }
 
 static void launch_gate_up(const void* xp, const void* wg, const void* wu, int P, int d, int f, int E,
-                           const int32_t* offsets, const RowTiles& rt, void* G, void* U, void* act, hipStream_t s) {
+                           const int32_t* offsets, const RowTiles& rt, void* G, void* U, void* act, hipStream_t s,
+                           unsigned long long* dbg = nullptr) {
   RowArgs p{};
   p.a = static_cast<const bf16_t*>(xp); p.lda = d;
   p.w0 = static_cast<const bf16_t*>(wg); p.w1 = static_cast<const bf16_t*>(wu);
   p.w_expert_stride = static_cast<long>(f) * d; p.ldw = d;
-  p.K = d; p.N = f; p.offsets = offsets; p.P = P; p.rt = rt;
+  p.K = d; p.N = f; p.offsets = offsets; p.P = P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
   p.out0 = static_cast<bf16_t*>(G); p.out1 = static_cast<bf16_t*>(U); p.out2 = static_cast<bf16_t*>(act); p.ldo = f;
   launch_row<kGateUp>(p, P, E, s);
 }
@@ -841,7 +839,7 @@ void ffn_fwd_bf16(const FfnFwdArgs& a) {
   RowArgs p{};
   p.a = static_cast<const bf16_t*>(a.act); p.lda = a.f;
   p.w0 = static_cast<const bf16_t*>(a.w_down); p.w_expert_stride = static_cast<long>(a.d) * a.f; p.ldw = a.f;
-  p.K = a.f; p.N = a.d; p.offsets = a.offsets; p.P = a.P; p.rt = rt;
+  p.K = a.f; p.N = a.d; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
   p.out0 = static_cast<bf16_t*>(a.yp); p.ldo = a.d;
   launch_row<kDown>(p, a.P, a.E, a.stream);
 }
@@ -865,7 +863,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     RowArgs p{};
     p.a = static_cast<const bf16_t*>(a.dyp); p.lda = a.d;
     p.w0 = static_cast<const bf16_t*>(a.w_down); p.w_expert_stride = static_cast<long>(a.d) * a.f; p.ldw = a.f;
-    p.K = a.d; p.N = a.f; p.offsets = a.offsets; p.P = a.P; p.rt = rt;
+    p.K = a.d; p.N = a.f; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = dgu; p.ldo = 2L * a.f; p.g = G; p.u = U;
     launch_row<kDAct>(p, a.P, a.E, a.stream);
   }
@@ -874,7 +872,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     p.a = dgu; p.lda = 2L * a.f;
     p.w0 = static_cast<const bf16_t*>(a.w_gate); p.w1 = static_cast<const bf16_t*>(a.w_up);
     p.w_expert_stride = static_cast<long>(a.f) * a.d; p.ldw = a.d;
-    p.K = a.f; p.N = a.d; p.offsets = a.offsets; p.P = a.P; p.rt = rt;
+    p.K = a.f; p.N = a.d; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dxp); p.ldo = a.d;
     launch_row<kDX>(p, a.P, a.E, a.stream);
   }
@@ -882,7 +880,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     WgradArgs p{};
     p.lhs = static_cast<const bf16_t*>(a.dyp); p.ld_lhs = a.d; p.M = a.d;
     p.rhs = static_cast<const bf16_t*>(a.act); p.ld_rhs = a.f; p.N = a.f;
-    p.offsets = a.offsets; p.E = a.E; p.P = a.P;
+    p.offsets = a.offsets; p.E = a.E; p.P = a.P; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_down); p.out1 = p.out0; p.m_split = a.d;
     launch_wgrad<0>(p, a.stream);
   }
@@ -890,7 +888,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     WgradArgs p{};
     p.lhs = dgu; p.ld_lhs = 2L * a.f; p.M = 2 * a.f;
     p.rhs = static_cast<const bf16_t*>(a.xp); p.ld_rhs = a.d; p.N = a.d;
-    p.offsets = a.offsets; p.E = a.E; p.P = a.P;
+    p.offsets = a.offsets; p.E = a.E; p.P = a.P; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_gate); p.out1 = static_cast<bf16_t*>(a.dw_up); p.m_split = a.f;
     launch_wgrad<1>(p, a.stream);
   }

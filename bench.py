@@ -169,7 +169,10 @@ def main():
     roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
                 "unit": dk["unit"], "frac": dk["frac"], "avg_ms": dk["avg_ms"],
                 "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant))}
-    gemm_names = [n for n in kernels if kernels[n].get("bound") in ("mfma", "alu")]
+    # everything the two grouped-GEMM entry points launch: the products, the device-side schedules and the
+    # reduction of split weight gradients
+    gemm_names = [n for n in kernels if kernels[n].get("bound") in ("mfma", "alu") or n.startswith("build_")
+                  or n.endswith("_reduce")]
     gemm_ms = sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in gemm_names)
     gemm_tflops = 18.0 * P * cfg.d * cfg.f / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     gemm_peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS

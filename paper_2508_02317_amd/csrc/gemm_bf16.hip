@@ -26,6 +26,7 @@
 // reduction dimension instead and have a host-known grid.
 // Workgroup ids are remapped so that consecutive tiles -- which share an expert's weights
 // -- run on the same XCD and hit its L2.
+#include <algorithm>
 #include <cstdlib>
 #include "moe_common.h"
 
@@ -495,6 +496,7 @@ struct RowArgs {
 };
 
 
+
 template <int KIND, class T>
 __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::kWavesPerSimd, T::kWavesPerSimd))) void row_grouped_kernel(RowArgs p) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -644,15 +646,98 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
 }
 
 // ============================================================================================
-// Weight-gradient kernel: out[e] (M x N) = lhs[rows of e, M]^T * rhs[rows of e, N]
+// Weight-gradient kernels: out[e] (M x N) = lhs[rows of e, M]^T * rhs[rows of e, N]
 // Output rows below `m_split` go to out0[e], the rest to out1[e] (gate / up share one launch).
+//
+// The reduction runs over the rows of an expert, so its length follows the routing.  Under skewed
+// routing a few experts own most rows; to keep every workgroup's share bounded, the rows of an expert
+// are cut into chunks of at most `chunk_rows`, one work item per (chunk, output tile).  An expert with a
+// single chunk is written directly.  The chunks of a split expert leave fp32 partial tiles in the
+// workspace, and a second kernel adds them in chunk order and rounds once -- the same result on every
+// run, unlike atomic accumulation.  Items are ordered by descending expert size so the long ones start first.
 // ============================================================================================
+struct WgradItems {
+  int32_t* count;        // [2]: number of items, number of split experts
+  int32_t* expert;       // [max_items]
+  int32_t* k0;           // [max_items] first row of the chunk
+  int32_t* k1;           // [max_items] one past its last row
+  int32_t* slot;         // [max_items] partial-tile slot, or -1: write the result directly
+  int32_t* split_expert; // [max_split]
+  int32_t* split_slot0;  // [max_split]
+  int32_t* split_n;      // [max_split]
+  int max_items, max_split, max_slots;
+};
+
+__global__ __launch_bounds__(1024) void build_wgrad_items_kernel(const int32_t* __restrict__ offsets, int E, int P,
+                                                                  int chunk_rows, WgradItems it) {
+  __shared__ int32_t cnt[kMaxExperts];      // rows per expert
+  __shared__ int32_t order[kMaxExperts];    // expert at each rank (descending size, ties by index)
+  __shared__ int32_t scan_items[kMaxExperts];
+  __shared__ int32_t scan_slots[kMaxExperts];
+  __shared__ int32_t scan_split[kMaxExperts];
+  const int e = threadIdx.x;
+  int begin = 0, c = -1;
+  if (e < E) {
+    begin = min(max(offsets[e], 0), P);
+    c = min(max(offsets[e + 1], begin), P) - begin;
+  }
+  cnt[e] = c;
+  __syncthreads();
+  if (e < E) {
+    int rank = 0;
+    for (int o = 0; o < E; ++o) rank += (cnt[o] > c || (cnt[o] == c && o < e)) ? 1 : 0;
+    order[rank] = e;
+  }
+  __syncthreads();
+  // thread r now speaks for the expert of rank r
+  int my_e = -1, my_n = 0, my_c = 0;
+  if (e < E) {
+    my_e = order[e];
+    my_c = cnt[my_e];
+    my_n = max(1, (my_c + chunk_rows - 1) / chunk_rows);
+  }
+  const int split = my_n > 1 ? 1 : 0;
+  scan_items[e] = my_n;
+  scan_slots[e] = split ? my_n : 0;
+  scan_split[e] = split;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int a = e >= o ? scan_items[e - o] : 0, b = e >= o ? scan_slots[e - o] : 0, d = e >= o ? scan_split[e - o] : 0;
+    __syncthreads();
+    scan_items[e] += a; scan_slots[e] += b; scan_split[e] += d;
+    __syncthreads();
+  }
+  if (e < E) {
+    const int first = scan_items[e] - my_n, slot0 = scan_slots[e] - (split ? my_n : 0), sidx = scan_split[e] - split;
+    const int row0 = min(max(offsets[my_e], 0), P);
+    // the host sizes the lists for the worst case; offsets that are not a monotone scan ending at P cannot overflow them
+    const bool fits = slot0 + my_n <= it.max_slots && sidx < it.max_split;
+    for (int j = 0; j < my_n && first + j < it.max_items; ++j) {
+      it.expert[first + j] = my_e;
+      it.k0[first + j] = row0 + (fits || !split ? j * chunk_rows : 0);
+      it.k1[first + j] = fits || !split ? row0 + min(my_c, (j + 1) * chunk_rows) : (j == 0 ? row0 + my_c : row0);
+      it.slot[first + j] = split && fits ? slot0 + j : (split && j > 0 ? -2 : -1);   // -2: nothing to do
+    }
+    if (split && fits) {
+      it.split_expert[sidx] = my_e;
+      it.split_slot0[sidx] = slot0;
+      it.split_n[sidx] = my_n;
+    }
+  }
+  if (e == 1023) {
+    it.count[0] = min(scan_items[1023], it.max_items);
+    it.count[1] = min(scan_split[1023], it.max_split);
+  }
+}
+
 struct WgradArgs {
   const bf16_t* lhs; long ld_lhs; int M;
   const bf16_t* rhs; long ld_rhs; int N;
-  const int32_t* offsets; int E; int P;
+  int E; int P;
+  WgradItems items;
   int tiles_m, tiles_n;
   bf16_t* out0; bf16_t* out1; int m_split;     // out1 rows are (m - m_split)
+  float* partial;                              // [max_slots][M][N]
   const bf16_t* zeros;     // at least 16 zero bytes
 };
 
@@ -661,11 +746,14 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int BM = T::BM, BN = T::BN, WM = T::WM, WN = T::WN, MI = T::MI, NI = T::NI;
   const int per_e = p.tiles_m * p.tiles_n;
-  const int v = xcd_remap(blockIdx.x, per_e * p.E);
+  const int n_items = p.items.count[0];
+  const int v = xcd_remap(blockIdx.x, per_e * n_items);
   if (v < 0) return;
-  const int e = v / per_e, mt = (v % per_e) / p.tiles_n, nt = v % p.tiles_n;
-  const int begin = min(max(p.offsets[e], 0), p.P);
-  const int end = min(max(p.offsets[e + 1], begin), p.P);
+  const int item = v / per_e, mt = (v % per_e) / p.tiles_n, nt = v % p.tiles_n;
+  const int e = p.items.expert[item];
+  const int slot = p.items.slot[item];
+  if (slot == -2) return;
+  const int begin = p.items.k0[item], end = p.items.k1[item];
   const int m0 = mt * BM, n0 = nt * BN;
   const int mrows = min(BM, p.M - m0), ncols = min(BN, p.N - n0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -695,6 +783,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   constexpr int LPR = WN / 8;
   constexpr int RPP = 64 / LPR;
   const int cl = wn * WN + (lane % LPR) * 8;
+  float* part = slot >= 0 ? p.partial + static_cast<long>(slot) * p.M * p.N : nullptr;
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     park_strip<T>(acc[mi], strip, lane);
@@ -707,12 +796,40 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
           float v[8];
           read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, v);
           const int m = m0 + rl;
-          bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
-                                      : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
-          *reinterpret_cast<uint4*>(out + n0 + cl) = pack8(v);
+          if (part) {
+            float* o = part + static_cast<long>(m) * p.N + n0 + cl;
+            *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+          } else {
+            bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
+                                        : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
+            *reinterpret_cast<uint4*>(out + n0 + cl) = pack8(v);
+          }
         }
       }
     }
+  }
+}
+
+// out[e] = bf16( sum over the chunks of a split expert, in chunk order, of its fp32 partial tiles )
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
+  const int s = blockIdx.y;
+  if (s >= p.items.count[1]) return;
+  const long mn = static_cast<long>(p.M) * p.N;
+  const int e = p.items.split_expert[s], n = p.items.split_n[s];
+  const float* part = p.partial + static_cast<long>(p.items.split_slot0[s]) * mn;
+  for (long i = (static_cast<long>(blockIdx.x) * 256 + threadIdx.x) * 8; i < mn; i += static_cast<long>(gridDim.x) * 2048) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < n; ++j) {
+      float v[8];
+      read8(part + j * mn + i, v);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[q] += v[q];
+    }
+    const int m = static_cast<int>(i / p.N), col = static_cast<int>(i % p.N);   // N is a multiple of 8: one row
+    bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
+                                : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
+    *reinterpret_cast<uint4*>(out + col) = pack8(acc);
   }
 }
 
@@ -740,10 +857,19 @@ static int row_bm() { return tile_choice() == 1 ? TileBig::BM : TileRow::BM; }
 // bound used for workspace sizing: the smallest row tile gives the longest list
 static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 
+// Rows per reduction chunk of the weight gradients: long enough that the fp32 partial tiles stay a small
+// part of the traffic, short enough that the largest work item is a small part of the launch.  At most
+// 2 * ceil(P / chunk) <= 64 partial slots can ever be needed (an expert is split only if it has more than
+// one chunk, and the chunks of split experts hold more than half their rows each but the last).
+static int wgrad_chunk_rows(int P) { return std::max(1024, static_cast<int>(align_up(static_cast<size_t>(ceil_div(P, 32)), 256))); }
+static int wgrad_max_items(int P, int E) { return E + ceil_div(P, wgrad_chunk_rows(P)); }
+static int wgrad_max_split(int P, int E) { return std::max(1, std::min(E, ceil_div(P, wgrad_chunk_rows(P)))); }
+static int wgrad_max_slots(int P) { return 2 * ceil_div(P, wgrad_chunk_rows(P)); }
+
 struct WsLayout {
-  size_t tiles_count, zeros, tiles_expert, tiles_row0, dgu, g, u, total;
+  size_t tiles_count, zeros, tiles_expert, tiles_row0, dgu, g, u, items, partial, total;
 };
-static WsLayout ws_layout(int P, int f, int E, bool need_dgu, bool need_gu) {
+static WsLayout ws_layout(int P, int d, int f, int E, bool need_dgu, bool need_gu) {
   WsLayout w{};
   size_t off = 0;
   w.tiles_count = off; off += 256;
@@ -755,14 +881,21 @@ static WsLayout ws_layout(int P, int f, int E, bool need_dgu, bool need_gu) {
   w.dgu = off; if (need_dgu) off += 2 * pf;
   w.g = off; if (need_gu) off += pf;
   w.u = off; if (need_gu) off += pf;
+  w.items = off; w.partial = off;
+  if (need_dgu) {                                      // backward only: weight-gradient schedule and partial tiles
+    const size_t it = align_up(static_cast<size_t>(wgrad_max_items(P, E)) * sizeof(int32_t), 256);
+    const size_t sp = align_up(static_cast<size_t>(wgrad_max_split(P, E)) * sizeof(int32_t), 256);
+    off += 256 + 4 * it + 3 * sp;
+    w.partial = off;
+    off += align_up(static_cast<size_t>(wgrad_max_slots(P)) * 2 * f * d * sizeof(float), 256);
+  }
   w.total = off + 256;
   return w;
 }
 
-size_t ffn_fwd_ws_bytes_bf16(int P, int d, int f, int E) { (void)d; return ws_layout(P, f, E, false, false).total; }
+size_t ffn_fwd_ws_bytes_bf16(int P, int d, int f, int E) { return ws_layout(P, d, f, E, false, false).total; }
 size_t ffn_bwd_ws_bytes_bf16(int P, int d, int f, int E, int have_saved) {
-  (void)d;
-  return ws_layout(P, f, E, true, !have_saved).total;
+  return ws_layout(P, d, f, E, true, !have_saved).total;
 }
 
 static RowTiles row_tiles_at(void* ws, const WsLayout& w, int P, int E) {
@@ -774,6 +907,25 @@ static RowTiles row_tiles_at(void* ws, const WsLayout& w, int P, int E) {
   rt.expert = reinterpret_cast<int32_t*>(b + w.tiles_expert);
   rt.row0 = reinterpret_cast<int32_t*>(b + w.tiles_row0);
   return rt;
+}
+
+static WgradItems wgrad_items_at(void* ws, const WsLayout& w, int P, int E) {
+  char* b = static_cast<char*>(ws) + w.items;
+  WgradItems it;
+  it.max_items = wgrad_max_items(P, E);
+  it.max_split = wgrad_max_split(P, E);
+  it.max_slots = wgrad_max_slots(P);
+  const size_t li = align_up(static_cast<size_t>(it.max_items) * sizeof(int32_t), 256);
+  const size_t ls = align_up(static_cast<size_t>(it.max_split) * sizeof(int32_t), 256);
+  it.count = reinterpret_cast<int32_t*>(b); b += 256;
+  it.expert = reinterpret_cast<int32_t*>(b); b += li;
+  it.k0 = reinterpret_cast<int32_t*>(b); b += li;
+  it.k1 = reinterpret_cast<int32_t*>(b); b += li;
+  it.slot = reinterpret_cast<int32_t*>(b); b += li;
+  it.split_expert = reinterpret_cast<int32_t*>(b); b += ls;
+  it.split_slot0 = reinterpret_cast<int32_t*>(b); b += ls;
+  it.split_n = reinterpret_cast<int32_t*>(b);
+  return it;
 }
 
 static unsigned padded_grid(int tiles) { return static_cast<unsigned>(ceil_div(tiles < 1 ? 1 : tiles, kXcds) * kXcds); }
@@ -808,9 +960,12 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   }
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
-  const unsigned grid = padded_grid(p.tiles_m * p.tiles_n * p.E);
+  const unsigned grid = padded_grid(p.tiles_m * p.tiles_n * p.items.max_items);
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : "wgrad_gate_up", (wgrad_kernel<WHICH, T>), dim3(grid), dim3(T::kThreads),
              T::kLdsBytes, s, p);
+  const long rblocks = (static_cast<long>(p.M) * p.N + 2047) / 2048;
+  const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 256L)), static_cast<unsigned>(p.items.max_split));
+  MOE_LAUNCH(WHICH == 0 ? "wgrad_down_reduce" : "wgrad_gate_up_reduce", wgrad_reduce_kernel, rgrid, dim3(256), 0, s, p);
 }
 
 template <int WHICH>
@@ -820,8 +975,7 @@ static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
 }
 
 static void launch_gate_up(const void* xp, const void* wg, const void* wu, int P, int d, int f, int E,
-                           const int32_t* offsets, const RowTiles& rt, void* G, void* U, void* act, hipStream_t s,
-                           unsigned long long* dbg = nullptr) {
+                           const int32_t* offsets, const RowTiles& rt, void* G, void* U, void* act, hipStream_t s) {
   RowArgs p{};
   p.a = static_cast<const bf16_t*>(xp); p.lda = d;
   p.w0 = static_cast<const bf16_t*>(wg); p.w1 = static_cast<const bf16_t*>(wu);
@@ -832,7 +986,7 @@ static void launch_gate_up(const void* xp, const void* wg, const void* wu, int P
 }
 
 void ffn_fwd_bf16(const FfnFwdArgs& a) {
-  const WsLayout w = ws_layout(a.P, a.f, a.E, false, false);
+  const WsLayout w = ws_layout(a.P, a.d, a.f, a.E, false, false);
   const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
   MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, row_bm(), rt);
   launch_gate_up(a.xp, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.g_save, a.u_save, a.act, a.stream);
@@ -846,7 +1000,7 @@ void ffn_fwd_bf16(const FfnFwdArgs& a) {
 
 void ffn_bwd_bf16(const FfnBwdArgs& a) {
   const bool recompute = a.g_save == nullptr;
-  const WsLayout w = ws_layout(a.P, a.f, a.E, true, recompute);
+  const WsLayout w = ws_layout(a.P, a.d, a.f, a.E, true, recompute);
   const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
   char* base = static_cast<char*>(a.ws);
   bf16_t* dgu = reinterpret_cast<bf16_t*>(base + w.dgu);       // [P, 2f] = [dG | dU]
@@ -876,11 +1030,15 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     p.out0 = static_cast<bf16_t*>(a.dxp); p.ldo = a.d;
     launch_row<kDX>(p, a.P, a.E, a.stream);
   }
+  const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
+  float* partial = reinterpret_cast<float*>(base + w.partial);
+  MOE_LAUNCH("build_wgrad_items", build_wgrad_items_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P,
+             wgrad_chunk_rows(a.P), items);
   {  // dWd[e] = dyp^T act
     WgradArgs p{};
     p.lhs = static_cast<const bf16_t*>(a.dyp); p.ld_lhs = a.d; p.M = a.d;
     p.rhs = static_cast<const bf16_t*>(a.act); p.ld_rhs = a.f; p.N = a.f;
-    p.offsets = a.offsets; p.E = a.E; p.P = a.P; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+    p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_down); p.out1 = p.out0; p.m_split = a.d;
     launch_wgrad<0>(p, a.stream);
   }
@@ -888,7 +1046,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     WgradArgs p{};
     p.lhs = dgu; p.ld_lhs = 2L * a.f; p.M = 2 * a.f;
     p.rhs = static_cast<const bf16_t*>(a.xp); p.ld_rhs = a.d; p.N = a.d;
-    p.offsets = a.offsets; p.E = a.E; p.P = a.P; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+    p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_gate); p.out1 = static_cast<bf16_t*>(a.dw_up); p.m_split = a.f;
     launch_wgrad<1>(p, a.stream);
   }

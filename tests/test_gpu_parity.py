@@ -234,6 +234,41 @@ def test_grouped_ffn_fwd_bwd(L, T, k, d, f, E, dt, kind):
     assert_close(to_np(dwd2), rdWd2, dt, "dw_down (recompute)")
 
 
+def test_ffn_bwd_weight_gradients_of_long_experts(L):
+    """Experts with more rows than one reduction chunk (1024 rows here) go through the split path: fp32
+    partial tiles per chunk, summed in chunk order.  Counts cover 3.x chunks, exactly one chunk, exactly two
+    chunks, one row over a chunk, short and empty experts."""
+    dt, d, f = "bf16", 136, 72
+    counts = np.array([3300, 1024, 0, 2048, 1025, 37, 0, 600], dtype=np.int64)
+    E, P = len(counts), int(counts.sum())
+    offs = np.zeros(E + 1, dtype=np.int32)
+    offs[1:] = np.cumsum(counts)
+    r = np.random.default_rng(11)
+    Xp = q(r.standard_normal((P, d)), dt).astype(np.float32)
+    Wg, Wu = q(r.standard_normal((E, f, d)) * 0.05, dt), q(r.standard_normal((E, f, d)) * 0.05, dt)
+    Wd = q(r.standard_normal((E, d, f)) * 0.05, dt)
+    G, U, A, _ = O.grouped_ffn_fwd(Xp, Wg, Wu, Wd, offs)
+    dYp = q(r.standard_normal((P, d)), dt)
+    Gq, Uq, Aq = q(G, dt), q(U, dt), q(A, dt)
+    rdXp, rdWg, rdWu, rdWd = O.grouped_ffn_bwd(dYp, Xp, Gq, Uq, Aq, Wg, Wu, Wd, offs)
+    args = (to_dev(dYp, dt), to_dev(Xp, dt), to_dev(Gq, dt), to_dev(Uq, dt), to_dev(Aq, dt), to_dev(Wg, dt),
+            to_dev(Wu, dt), to_dev(Wd, dt), to_dev(offs))
+    dxp, dwg, dwu, dwd = L.moe_grouped_gemm_swiglu_bwd(*args)
+    assert_close(to_np(dxp), rdXp, dt, "dxp")
+    for e in range(E):
+        say("  expert %d rows %d" % (e, counts[e]))
+        if counts[e] == 0:
+            assert not to_np(dwg)[e].any() and not to_np(dwu)[e].any() and not to_np(dwd)[e].any()
+            continue
+        assert_close(to_np(dwg)[e], rdWg[e], dt, "dw_gate[%d]" % e)
+        assert_close(to_np(dwu)[e], rdWu[e], dt, "dw_up[%d]" % e)
+        assert_close(to_np(dwd)[e], rdWd[e], dt, "dw_down[%d]" % e)
+    # the split path is deterministic: a second run gives the same bits
+    again = L.moe_grouped_gemm_swiglu_bwd(*args)
+    for a, b in zip((dxp, dwg, dwu, dwd), again):
+        assert np.array_equal(to_np(a), to_np(b))
+
+
 def test_ffn_zero_rows_writes_zero_weight_gradients(L):
     import torch
     E, d, f = 3, 64, 64

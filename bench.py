@@ -147,6 +147,7 @@ def main():
         step()
     torch.cuda.synchronize()
     prof = L.moe_profile_report()
+    sclk = L.moe_profile_shader_clock() if cfg.dtype == "bf16" else {}
     L.moe_profile_enable(0)
 
     work = kernel_work(cfg, P)
@@ -162,6 +163,9 @@ def main():
                 peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
                 entry.update(bound=bound, achieved=round(amount / (avg_ms * 1e-3) / 1e12, 2), unit="TFLOP/s", peak=peak)
             entry["frac"] = round(entry["achieved"] / entry["peak"], 4)
+        if sclk.get(name):
+            # shader clock a workgroup in the middle of the launch ran at (nominal 2400 MHz, which `peak` assumes)
+            entry["shader_clock_mhz"] = round(sclk[name], 1)
         kernels[name] = entry
     dominant = max((n for n in kernels if "frac" in kernels[n]),
                    key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
@@ -169,6 +173,8 @@ def main():
     roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
                 "unit": dk["unit"], "frac": dk["frac"], "avg_ms": dk["avg_ms"],
                 "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant))}
+    if "shader_clock_mhz" in dk:
+        roofline["shader_clock_mhz"] = dk["shader_clock_mhz"]
     # everything the two grouped-GEMM entry points launch: the products, the device-side schedules and the
     # reduction of split weight gradients
     gemm_names = [n for n in kernels if kernels[n].get("bound") in ("mfma", "alu") or n.startswith("build_")

@@ -166,9 +166,16 @@ int32_t moe_unpermute_combine_bwd(const void* dy, const void* yp, int dtype, int
  * moe_profile_report: waits for the recorded events, writes one line per kernel
  * "name launches total_milliseconds\n" into buf ([host], cap bytes, NUL-terminated,
  * truncated if too small), clears the records and returns the size needed.
+ * moe_profile_shader_clock: while profiling is on, the middle workgroup of each grouped-GEMM launch
+ * (bf16 element type) measures the shader clock it ran at (shader-clock ticks against the fixed
+ * 100 MHz reference counter, start to end of that workgroup).  Writes the latest value in MHz for
+ * kernel i = 0..5 (gate/up, down, dA, dXp, dW_down, dW_gate/up) to mhz[i] ([host], n entries;
+ * 0.0 where nothing was recorded or i >= 6).  Call it after the launch stream has been
+ * synchronised; it copies 96 bytes from the device.
  */
 int32_t moe_profile_enable(int on);
 size_t moe_profile_report(char* buf, size_t cap);
+int32_t moe_profile_shader_clock(double* mhz, int n);
 
 #ifdef __cplusplus
 }

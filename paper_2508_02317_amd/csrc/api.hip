@@ -32,6 +32,7 @@ namespace {
 struct ProfRecord { const char* name; hipEvent_t start, stop; };
 std::mutex g_prof_mutex;
 bool g_prof_on = false;
+unsigned long long* g_prof_clock = nullptr;   // device, kClockSlots x {shader ticks, 100 MHz ticks}
 std::vector<ProfRecord> g_prof_records;     // records in use
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;   // events ready for reuse
 }  // namespace
@@ -58,6 +59,10 @@ ProfScope::~ProfScope() {
   (void)hipEventRecord(g_prof_records[slot_].stop, stream_);
 }
 
+unsigned long long* prof_clock_slot(int which) {
+  return (g_prof_on && g_prof_clock && which >= 0 && which < kClockSlots) ? g_prof_clock + 2 * which : nullptr;
+}
+
 static int32_t check_ffn_dims(const char* who, int dtype, int P, int d, int f, int E) {
   MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, dtype);
   MOE_REQUIRE(P >= 0 && d > 0 && f > 0 && E > 0, MOE_ERR_INVALID_ARG, "%s: need P >= 0, d, f, E > 0 (P=%d d=%d f=%d E=%d)", who, P, d, f, E);
@@ -76,9 +81,30 @@ extern "C" const char* moe_last_error(void) { return g_error; }
 
 extern "C" int32_t moe_profile_enable(int on) {
   std::lock_guard<std::mutex> lock(g_prof_mutex);
+  if (on && !g_prof_clock) {
+    if (hipMalloc(reinterpret_cast<void**>(&g_prof_clock), kClockSlots * 2 * sizeof(unsigned long long)) != hipSuccess) {
+      g_prof_clock = nullptr;
+      return fail(MOE_ERR_HIP, "moe_profile_enable: cannot allocate the clock slots");
+    }
+  }
+  if (on && hipMemset(g_prof_clock, 0, kClockSlots * 2 * sizeof(unsigned long long)) != hipSuccess)
+    return fail(MOE_ERR_HIP, "moe_profile_enable: cannot clear the clock slots");
   for (auto& r : g_prof_records) g_prof_pool.emplace_back(r.start, r.stop);
   g_prof_records.clear();
   g_prof_on = on != 0;
+  return MOE_OK;
+}
+
+extern "C" int32_t moe_profile_shader_clock(double* mhz, int n) {
+  MOE_REQUIRE(mhz != nullptr && n >= 0, MOE_ERR_INVALID_ARG, "moe_profile_shader_clock: null output or negative count");
+  unsigned long long host[kClockSlots * 2] = {};
+  {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (g_prof_clock && hipMemcpy(host, g_prof_clock, sizeof(host), hipMemcpyDeviceToHost) != hipSuccess)
+      return fail(MOE_ERR_HIP, "moe_profile_shader_clock: copy from the device failed");
+  }
+  for (int i = 0; i < n; ++i)
+    mhz[i] = (i < kClockSlots && host[2 * i + 1] > 0) ? 100.0 * static_cast<double>(host[2 * i]) / static_cast<double>(host[2 * i + 1]) : 0.0;
   return MOE_OK;
 }
 

@@ -6,10 +6,10 @@
 //     WM x WN sub-tile made of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, fp32
 //     accumulators kept in registers for the whole reduction);
 //   * the reduction dimension is walked in BK-wide slabs through a 3-stage LDS ring that is
-//     filled by direct global->LDS loads (no staging registers); two to three slabs are in
-//     flight behind the one being multiplied, the MFMA operands are double-buffered in
-//     registers one reduction step ahead, and one barrier per slab separates writers from
-//     readers; a partial last slab reads zeros for the reduction indices it does not have;
+//     filled by direct global->LDS loads (no staging registers); two slabs are in flight
+//     behind the one being multiplied, the MFMA operands are double-buffered in registers one
+//     reduction step ahead, and one barrier per slab separates writers from readers; a partial
+//     last slab reads zeros for the reduction indices it does not have;
 //   * results leave through LDS as well, so that all global stores (and the loads of the
 //     saved pre-activations in the fused SwiGLU derivative) are 16 bytes per lane and
 //     contiguous along rows;
@@ -246,9 +246,10 @@ __device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::N
 //     barrier: slab kt+1 is visible to all, and nobody reads the stage of slab kt any more
 //     refill that stage with slab kt+S; read step 0 of slab kt+1 | MFMAs of the last step of slab kt
 // so up to S-1 slabs are in flight behind the slab being multiplied.  The loop over slabs is
-// unrolled S times so that every LDS address is "register + constant": on this hardware every
-// VALU instruction and every LDS read takes issue time away from the MFMAs of the same SIMD
-// (measured: about 16 cycles per 16-byte LDS read against 32 per MFMA).
+// unrolled S times so that every LDS address is "register + constant" and no address arithmetic
+// competes with the MFMAs for issue slots.  What limits the stream is the number of L2 requests a
+// CU can have outstanding (about 128, whatever the ring depth): 64-byte row pieces (BK = 32) give
+// about 30 bytes per clock and CU on L2 hits, 128-byte pieces (BK = 64) about 60.
 template <class T, bool A_KS, bool B_KS>
 struct MainLoop {
   typedef Dma<A_KS, T::BM, T::BK, T::kWaves> DmaA;
@@ -493,6 +494,7 @@ struct RowArgs {
   const bf16_t* g;         // kDAct: saved pre-activations
   const bf16_t* u;
   const bf16_t* zeros;     // at least 16 zero bytes (source of out-of-range reduction indices)
+  unsigned long long* clock;   // null, or where the first workgroup records the clock it ran at
 };
 
 
@@ -504,6 +506,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   const int n_row_tiles = p.rt.count[0];
   const int v = xcd_remap(blockIdx.x, n_row_tiles * p.n_tiles_n);
   if (v < 0) return;
+  ClockStamp stamp(p.clock);
   const int mt = v / p.n_tiles_n, nt = v % p.n_tiles_n;
   const int e = p.rt.expert[mt];
   const int row0 = p.rt.row0[mt];
@@ -739,6 +742,7 @@ struct WgradArgs {
   bf16_t* out0; bf16_t* out1; int m_split;     // out1 rows are (m - m_split)
   float* partial;                              // [max_slots][M][N]
   const bf16_t* zeros;     // at least 16 zero bytes
+  unsigned long long* clock;   // null, or where the first workgroup records the clock it ran at
 };
 
 template <int WHICH, class T>   // WHICH 0: dW_down, 1: [dW_gate; dW_up] (separate symbols so profiles tell them apart)
@@ -749,6 +753,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   const int n_items = p.items.count[0];
   const int v = xcd_remap(blockIdx.x, per_e * n_items);
   if (v < 0) return;
+  ClockStamp stamp(p.clock);
   const int item = v / per_e, mt = (v % per_e) / p.tiles_n, nt = v % p.tiles_n;
   const int e = p.items.expert[item];
   const int slot = p.items.slot[item];
@@ -840,10 +845,11 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
 // with a few hundred rows waste little; the weight side is 256 wide.
 typedef Tile<128, 256, 32, 2, 2, 3> TileRow;           // 72 KiB of LDS: two 4-wave workgroups per CU
 typedef Tile<128, 256, 32, 2, 2, 3> TileWgrad;
-typedef Tile<128, 256, 64, 2, 4, 3> TileBig;           // 144 KiB of LDS: one 8-wave workgroup per CU, 64 x 64 per wave, 128-byte row pieces
+typedef Tile<128, 256, 64, 2, 4, 3> TileWide;           // 144 KiB of LDS: one 8-wave workgroup per CU, 64 x 64 per wave, 128-byte row pieces
 
-// 0 = default.  MOE_GEMM_TILE=1 in the environment selects the 256 x 256 variant for every product
-// (a tuning knob; the measured difference on the 30B-class shapes is a few percent either way).
+// 0 = default.  MOE_GEMM_TILE=1 in the environment selects the 64-wide-slab variant for every product: its
+// 128-byte row pieces halve the number of L2 requests of reduction-contiguous operands (a tuning knob; on the
+// 30B-class shapes it is 3 % faster for the gate/up product and 10-25 % slower for the other five).
 static int tile_choice() {
   static int choice = -1;
   if (choice < 0) {
@@ -853,7 +859,7 @@ static int tile_choice() {
   return choice;
 }
 
-static int row_bm() { return tile_choice() == 1 ? TileBig::BM : TileRow::BM; }
+static int row_bm() { return tile_choice() == 1 ? TileWide::BM : TileRow::BM; }
 // bound used for workspace sizing: the smallest row tile gives the longest list
 static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 
@@ -940,13 +946,14 @@ static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
     attr_set = true;
   }
   p.n_tiles_n = ceil_div(p.N, KIND == kGateUp ? T::BN / 2 : T::BN);
+  p.clock = prof_clock_slot(KIND);
   const unsigned grid = padded_grid((ceil_div(P, T::BM) + E) * p.n_tiles_n);
   MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);
 }
 
 template <int KIND>
 static void launch_row(const RowArgs& p, int P, int E, hipStream_t s) {
-  if (tile_choice() == 1) launch_row_t<KIND, TileBig>(p, P, E, s);
+  if (tile_choice() == 1) launch_row_t<KIND, TileWide>(p, P, E, s);
   else launch_row_t<KIND, TileRow>(p, P, E, s);
 }
 
@@ -958,6 +965,7 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
     attr_set = true;
   }
+  p.clock = prof_clock_slot(4 + WHICH);
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
   const unsigned grid = padded_grid(p.tiles_m * p.tiles_n * p.items.max_items);
@@ -970,7 +978,7 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
 
 template <int WHICH>
 static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
-  if (tile_choice() == 1) launch_wgrad_t<WHICH, TileBig>(p, s);
+  if (tile_choice() == 1) launch_wgrad_t<WHICH, TileWide>(p, s);
   else launch_wgrad_t<WHICH, TileWgrad>(p, s);
 }
 

@@ -29,6 +29,23 @@ struct ProfScope {
     hipLaunchKernelGGL(kern, grid, block, shmem, stream, __VA_ARGS__);     \
   } while (0)
 
+// While profiling is on, the workgroup in the middle of the grid of each grouped-GEMM launch records how
+// many shader-clock ticks and how many ticks of the fixed 100 MHz reference passed between its start and
+// its end: the clock these kernels actually ran at (the first workgroups of a launch still see the higher
+// clock left by whatever ran before).  Returns the two-word device slot of GEMM kernel `which` (0..5), or null.
+constexpr int kClockSlots = 6;
+unsigned long long* prof_clock_slot(int which);
+struct ClockStamp {
+  unsigned long long* out_;
+  unsigned long long ref0_, clk0_;
+  __device__ __forceinline__ explicit ClockStamp(unsigned long long* out) : out_(blockIdx.x == gridDim.x / 2 ? out : nullptr), ref0_(0), clk0_(0) {
+    if (out_) { ref0_ = wall_clock64(); clk0_ = clock64(); }
+  }
+  __device__ __forceinline__ ~ClockStamp() {
+    if (out_ && threadIdx.x == 0) { out_[0] = clock64() - clk0_; out_[1] = wall_clock64() - ref0_; }
+  }
+};
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

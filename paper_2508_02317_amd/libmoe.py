@@ -26,7 +26,7 @@ EXPORTS = [
     "moe_grouped_gemm_swiglu_fwd_workspace_bytes", "moe_grouped_gemm_swiglu_fwd",
     "moe_grouped_gemm_swiglu_bwd_workspace_bytes", "moe_grouped_gemm_swiglu_bwd",
     "moe_unpermute_combine_fwd", "moe_unpermute_combine_bwd",
-    "moe_profile_enable", "moe_profile_report",
+    "moe_profile_enable", "moe_profile_report", "moe_profile_shader_clock",
 ]
 
 
@@ -75,6 +75,8 @@ def _load():
     lib.moe_unpermute_combine_bwd.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.moe_profile_enable.restype = ctypes.c_int32
     lib.moe_profile_enable.argtypes = [i32]
+    lib.moe_profile_shader_clock.restype = ctypes.c_int32
+    lib.moe_profile_shader_clock.argtypes = [ctypes.POINTER(ctypes.c_double), i32]
     lib.moe_profile_report.restype = sz
     lib.moe_profile_report.argtypes = [ctypes.c_char_p, sz]
     return lib
@@ -93,6 +95,14 @@ def moe_last_error():
 
 def moe_profile_enable(on):
     _check(lib.moe_profile_enable(int(bool(on))))
+
+
+def moe_profile_shader_clock():
+    """MHz the middle workgroup of each grouped-GEMM launch ran at (0.0 where nothing was recorded)."""
+    names = ("ffn_gate_up", "ffn_down", "ffn_dact", "ffn_dx", "wgrad_down", "wgrad_gate_up")
+    out = (ctypes.c_double * len(names))()
+    _check(lib.moe_profile_shader_clock(out, len(names)))
+    return {n: float(v) for n, v in zip(names, out)}
 
 
 def moe_profile_report():

@@ -30,7 +30,9 @@ GPU receives) and nothing is rounded afterwards.
 Pins (tests/test_oracle_*.py): dense brute-force evaluation (oracle/moe_brute.py),
 closed forms and special cases (identical experts -> plain SwiGLU MLP, k=1 -> w=1 and
 dz=0, k=E -> full softmax mixture), permutation bijection, weight sums, central finite
-differences for every gradient.  No function here is "parity unpinned"; what stays
+differences for every gradient (the router linear and the whole-block gradient included:
+finite differences of the loss through the logits with the selection held fixed, and scalar
+loops).  No function here is "parity unpinned"; what stays
 unpinned is only whether the paper's own model renormalises and its weight dims 1-2,
 because the paper does not say.
 """
@@ -240,6 +242,39 @@ def moe_layer_bwd(fwd, dY, logits, Wg, Wu, Wd, renorm=1):
     dX = unpermute_combine_fwd(dXp, None, fwd["row_of_pair"], T, k)
     dlogits = None if logits is None else route_topk_bwd(dw, w, idx, logits, E, renorm)
     return dict(dYp=dYp, dw=dw, dXp=dXp, dWg=dWg, dWu=dWu, dWd=dWd, dX=dX, dlogits=dlogits)
+
+
+# --------------------------------------------------------------------------- router linear
+# The router that produces the logits is a bias-free linear map of the hidden state (Sec. 3.2.3
+# speaks only of "routing"; a linear gate is the standard reading).  Weight layout, again a
+# reading: W_router [E, d] ("out-features x in-features"), row e = the gate vector of expert e.
+
+def router_logits(X, Wr):
+    """z[t, e] = <X[t, :], Wr[e, :]>."""
+    return np.asarray(X, dtype=np.float64) @ np.asarray(Wr, dtype=np.float64).T
+
+
+def router_bwd(dlogits, X, Wr):
+    """Backward of router_logits for an upstream dlogits [T, E]:
+    dWr[e, :] = sum_t dlogits[t, e] X[t, :];   dX_router[t, :] = sum_e dlogits[t, e] Wr[e, :]."""
+    dz = np.asarray(dlogits, dtype=np.float64)
+    dWr = dz.T @ np.asarray(X, dtype=np.float64)
+    dXr = dz @ np.asarray(Wr, dtype=np.float64)
+    return dXr, dWr
+
+
+def moe_block_bwd(fwd, dY, logits, X, Wr, Wg, Wu, Wd, renorm=1):
+    """Backward of the whole block, hidden state in to hidden-state gradient out, for
+    L = sum(dY * Y) with logits = router_logits(X, Wr): the layer backward plus the router
+    term.  The top-k selection is treated as constant.  Returns the layer's dict with dX
+    replaced by the full gradient, plus dX_expert, dX_router and dWr."""
+    out = moe_layer_bwd(fwd, dY, logits, Wg, Wu, Wd, renorm)
+    dXr, dWr = router_bwd(out["dlogits"], X, Wr)
+    out["dX_expert"] = out["dX"]
+    out["dX_router"] = dXr
+    out["dX"] = out["dX"] + dXr
+    out["dWr"] = dWr
+    return out
 
 
 # --------------------------------------------------------------------------- sampled outputs

@@ -256,6 +256,63 @@ def test_gradients_by_finite_differences_on_brute_loss(k, renorm):
             assert bwd["dlogits"].reshape(-1)[i] == pytest.approx(v, rel=2e-6, abs=2e-7), ("z", i)
 
 
+# ------------------------------------------------------------------ router linear, whole block
+
+def _logits_by_loops(X, Wr):
+    """z[t][e] = sum_i X[t][i] * Wr[e][i] with plain Python loops (no library product)."""
+    return [[sum(float(X[t][i]) * float(Wr[e][i]) for i in range(len(X[t]))) for e in range(len(Wr))]
+            for t in range(len(X))]
+
+
+def test_router_linear_vs_scalar_loops():
+    r = np.random.default_rng(41)
+    T, d, E = 5, 7, 3
+    X, Wr, dz = r.standard_normal((T, d)), r.standard_normal((E, d)), r.standard_normal((T, E))
+    assert np.allclose(O.router_logits(X, Wr), np.array(_logits_by_loops(X, Wr)), rtol=1e-13, atol=1e-13)
+    dXr, dWr = O.router_bwd(dz, X, Wr)
+    for t in range(T):
+        for i in range(d):
+            assert dXr[t, i] == pytest.approx(sum(dz[t, e] * Wr[e, i] for e in range(E)), rel=1e-12, abs=1e-13)
+    for e in range(E):
+        for i in range(d):
+            assert dWr[e, i] == pytest.approx(sum(dz[t, e] * X[t, i] for t in range(T)), rel=1e-12, abs=1e-13)
+    # a one-hot upstream gradient picks one row of Wr / one row of X
+    one = np.zeros((T, E)); one[2, 1] = 1.0
+    dXr, dWr = O.router_bwd(one, X, Wr)
+    assert np.array_equal(dXr[2], Wr[1]) and not dXr[[0, 1, 3, 4]].any()
+    assert np.array_equal(dWr[1], X[2]) and not dWr[[0, 2]].any()
+
+
+@pytest.mark.parametrize("k,renorm", [(2, 1), (3, 0)])
+def test_whole_block_gradient_by_finite_differences(k, renorm):
+    """L(X, Wr) = sum(dY * Y) with the logits recomputed from X and Wr by scalar loops and the dense
+    brute-force layer on top: its finite differences w.r.t. X and Wr must equal the block backward
+    (expert path + router path).  Tokens whose top-k boundary is close are left out, as the selection
+    is treated as constant."""
+    T, d, E, f = 6, 4, 4, 5
+    X, _, Wg, Wu, Wd, dY = _rand_layer(50 + k, T, d, E, f, wscale=0.7)
+    Wr = np.random.default_rng(60 + k).standard_normal((E, d))
+    z = O.router_logits(X, Wr)
+    zs = np.sort(z, axis=1)[:, ::-1]
+    safe = [t for t in range(T) if k == E or zs[t, k - 1] - zs[t, k] > 1e-3]
+    assert len(safe) >= 3
+    fwd = O.moe_layer_fwd(X, z, Wg, Wu, Wd, k, renorm)
+    blk = O.moe_block_bwd(fwd, dY, z, X, Wr, Wg, Wu, Wd, renorm)
+    assert np.allclose(blk["dX"], blk["dX_expert"] + blk["dX_router"])
+    loss = lambda: B.loss_dense(X, _logits_by_loops(X, Wr), Wg, Wu, Wd, dY, k, renorm)
+    fd = _fd(loss, X, picks=[t * d + i for t in safe for i in range(d)])
+    for i, v in fd.items():
+        assert blk["dX"].reshape(-1)[i] == pytest.approx(v, rel=5e-6, abs=5e-7), ("X", i)
+    if len(safe) == T:                                   # dWr sums over every token
+        fd = _fd(loss, Wr)
+        for i, v in fd.items():
+            assert blk["dWr"].reshape(-1)[i] == pytest.approx(v, rel=5e-6, abs=5e-7), ("Wr", i)
+    # with k = 1 and renormalised weights the logits carry no gradient: the router term vanishes
+    fwd1 = O.moe_layer_fwd(X, z, Wg, Wu, Wd, 1, 1)
+    blk1 = O.moe_block_bwd(fwd1, dY, z, X, Wr, Wg, Wu, Wd, 1)
+    assert not blk1["dX_router"].any() and not blk1["dWr"].any()
+
+
 def test_dlogits_invariants_and_linearity():
     X, z, Wg, Wu, Wd, dY = _rand_layer(30, 12, 5, 6, 4)
     for renorm in (0, 1):

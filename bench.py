@@ -58,6 +58,11 @@ def kernel_work(cfg, P):
         "permute_gather": ("hbm", (T + P) * d * s + 2 * P * 4),
         "combine_fwd": ("hbm", (P + T) * d * s + P * 8),
         "combine_bwd": ("hbm", (T + 2 * P) * d * s + P * 12),
+        # router linear (--router): skinny products, bound by reading / writing the [T, d] side
+        "router_logits": ("hbm", T * d * s + E * d * s + T * E * 4),
+        "router_cast_dz": ("hbm", T * E * 6),
+        "router_dx": ("hbm", 2 * T * d * s + T * E * 2 + E * d * s),
+        "wgrad_router": ("hbm", T * d * s + T * E * 2 + E * d * s),
     }
     return work
 
@@ -70,6 +75,9 @@ def main():
     ap.add_argument("--workload", default="a3b_8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-save-gu", action="store_true", help="backward recomputes G and U")
+    ap.add_argument("--router", action="store_true",
+                    help="start from hidden states: the router linear and its backward are part of the step "
+                         "(the default step starts from given logits, as the metric's path does)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -116,8 +124,12 @@ def main():
     else:
         Xh = inp["X"]
         x = dev(Xh)
+    w_router = None
+    if args.router:
+        assert not prerouted, "--router needs a workload that routes"
+        w_router = dev(np.ascontiguousarray(inp["Wr"].T))             # [E, d]
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, wg, wu, wd, renorm=cfg.renorm, prerouted=prerouted,
-                     save_gu=not args.no_save_gu)
+                     save_gu=not args.no_save_gu, w_router=w_router)
     P = layer.P
     print("[bench] %s: inputs ready in %.1f s" % (cfg.name, time.time() - t0), file=sys.stderr, flush=True)
 
@@ -189,7 +201,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "k": cfg.k, "f": cfg.f, "P": P,
-                   "renorm": cfg.renorm, "save_gu": not args.no_save_gu,
+                   "renorm": cfg.renorm, "save_gu": not args.no_save_gu, "router_linear_in_step": bool(args.router),
                    "unit_note": "routed rows/s" if prerouted else "tokens/s"},
         "roofline": roofline,
         "grouped_gemm": {"tflops": round(gemm_tflops, 2), "frac_of_peak": round(gemm_tflops / gemm_peak, 4),

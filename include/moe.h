@@ -158,6 +158,28 @@ int32_t moe_unpermute_combine_bwd(const void* dy, const void* yp, int dtype, int
                                   void* dyp, float* dw, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Router linear: the bias-free gate that turns hidden states into the logits moe_route_topk
+ * consumes, and its backward, so that the library covers the block from hidden states in
+ * to hidden-state gradient out (Sec. 3.2.3 speaks of routing only; a linear gate is the reading).
+ *   w_router [E, d] (row e = gate vector of expert e; same element type as x), device.
+ *   logits[t, e] = <x[t, :], w_router[e, :]>, fp32 accumulation, fp32 output [T, E].
+ * Backward for an upstream dlogits [T, E] f32 (e.g. from moe_route_topk_bwd):
+ *   dw_router[e, :] = sum_t dlogits[t, e] x[t, :]           [E, d], element type of x, overwritten
+ *   dx[t, :] (+)= sum_e dlogits[t, e] w_router[e, :]        [T, d]; accumulate != 0 adds to what
+ *                                                           dx holds (the expert-path gradient)
+ * For bf16 the logit gradient is rounded to bf16 once before the two products.
+ * Limits: d, E > 0, E <= 1024; bf16 needs d and E multiples of 8 (MOE_ERR_UNSUPPORTED otherwise).
+ * T == 0: nothing is read; dw_router is written as zeros.  Workspaces as for the other calls.
+ */
+size_t moe_router_logits_workspace_bytes(int dtype, int T, int d, int E);
+int32_t moe_router_logits(const void* x, const void* w_router, int dtype, int T, int d, int E,
+                          float* logits, void* ws, size_t ws_bytes, void* stream);
+size_t moe_router_bwd_workspace_bytes(int dtype, int T, int d, int E);
+int32_t moe_router_bwd(const float* dlogits, const void* x, const void* w_router, int dtype,
+                       int T, int d, int E, int accumulate, void* dx, void* dw_router,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Per-kernel timing for measurement harnesses (not part of the layer's arithmetic).
  * moe_profile_enable(1): from now on every kernel the library launches is bracketed by a
  * pair of HIP events recorded on the launch stream (the library creates the events it

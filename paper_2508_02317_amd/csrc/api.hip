@@ -183,3 +183,61 @@ extern "C" int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, 
   if (dtype == MOE_BF16) ffn_bwd_bf16(a); else ffn_bwd_f32(a);
   return check_launch("moe_grouped_gemm_swiglu_bwd");
 }
+
+// ---- router linear -----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+static int32_t check_router_dims(const char* who, int dtype, int T, int d, int E) {
+  MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, dtype);
+  MOE_REQUIRE(T >= 0 && d > 0 && E > 0, MOE_ERR_INVALID_ARG, "%s: need T >= 0, d, E > 0 (T=%d d=%d E=%d)", who, T, d, E);
+  MOE_REQUIRE(E <= kMaxExperts, MOE_ERR_UNSUPPORTED, "%s: E=%d above the built maximum %d", who, E, kMaxExperts);
+  MOE_REQUIRE(dtype == MOE_F32 || (d % 8 == 0 && E % 8 == 0), MOE_ERR_UNSUPPORTED, "%s: d=%d and E=%d must be multiples of 8 for bf16", who, d, E);
+  return MOE_OK;
+}
+
+extern "C" size_t moe_router_logits_workspace_bytes(int dtype, int T, int d, int E) {
+  if (T <= 0 || d <= 0 || E <= 0) return 256;
+  return dtype == MOE_BF16 ? router_fwd_ws_bytes_bf16(T, d, E) : 256;
+}
+
+extern "C" size_t moe_router_bwd_workspace_bytes(int dtype, int T, int d, int E) {
+  if (T <= 0 || d <= 0 || E <= 0) return 256;
+  return dtype == MOE_BF16 ? router_bwd_ws_bytes_bf16(T, d, E) : 256;
+}
+
+extern "C" int32_t moe_router_logits(const void* x, const void* w_router, int dtype, int T, int d, int E, float* logits,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_router_dims("router_logits", dtype, T, d, E)) return rc;
+  if (T == 0) return MOE_OK;
+  MOE_REQUIRE(x && w_router && logits, MOE_ERR_INVALID_ARG, "router_logits: null pointer");
+  MOE_REQUIRE(aligned16(x) && aligned16(w_router) && aligned16(logits), MOE_ERR_INVALID_ARG, "router_logits: tensors must be 16-byte aligned");
+  const size_t need = moe_router_logits_workspace_bytes(dtype, T, d, E);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "router_logits: workspace null, misaligned or smaller than %zu bytes", need);
+  RouterFwdArgs a{x, w_router, T, d, E, logits, ws, static_cast<hipStream_t>(stream)};
+  if (dtype == MOE_BF16) router_fwd_bf16(a); else router_fwd_f32(a);
+  return check_launch("moe_router_logits");
+}
+
+extern "C" int32_t moe_router_bwd(const float* dlogits, const void* x, const void* w_router, int dtype, int T, int d, int E,
+                                  int accumulate, void* dx, void* dw_router, void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_router_dims("router_bwd", dtype, T, d, E)) return rc;
+  MOE_REQUIRE(w_router && dw_router, MOE_ERR_INVALID_ARG, "router_bwd: null weight or weight-gradient pointer");
+  MOE_REQUIRE(T == 0 || (dlogits && x && dx), MOE_ERR_INVALID_ARG, "router_bwd: null pointer");
+  MOE_REQUIRE(aligned16(dlogits) && aligned16(x) && aligned16(w_router) && aligned16(dx) && aligned16(dw_router), MOE_ERR_INVALID_ARG,
+              "router_bwd: tensors must be 16-byte aligned");
+  const size_t need = moe_router_bwd_workspace_bytes(dtype, T, d, E);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "router_bwd: workspace null, misaligned or smaller than %zu bytes", need);
+  if (T == 0) {   // no rows: the weight gradient is all zeros (a fill kernel, not a memset node: callers may capture this)
+    const size_t words = static_cast<size_t>(E) * d * elem_size(dtype) / 4;
+    hipLaunchKernelGGL(zero_words_kernel, dim3(static_cast<unsigned>((words + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint32_t*>(dw_router), words);
+    return check_launch("moe_router_bwd");
+  }
+  RouterBwdArgs a{dlogits, x, w_router, T, d, E, accumulate != 0, dx, dw_router, ws, static_cast<hipStream_t>(stream)};
+  if (dtype == MOE_BF16) router_bwd_bf16(a); else router_bwd_f32(a);
+  return check_launch("moe_router_bwd");
+}
+

@@ -266,9 +266,12 @@ struct MainLoop {
   char* lds;
   const char* zeros;
   int nslabs, nfull, K, wave;
+  int rot;                   // the reduction starts at slab `rot` and wraps around
 
-  __device__ __forceinline__ void issue(int slab, int stage) {
+  __device__ __forceinline__ void issue(int step, int stage) {
     char* st = lds + stage * T::kStageBytes;
+    int slab = step + rot;
+    if (slab >= nslabs) slab -= nslabs;
     if (slab < nfull) {
       da.issue(slab, st, wave);
       db.issue(slab, st + T::kABytes, wave);
@@ -338,13 +341,14 @@ struct MainLoop {
 
   __device__ __forceinline__ void run(const Operand* opA, const Operand* opB, int nseg, int K_, char* lds_,
                                       const bf16_t* zeros_, const int (&a_row)[T::MI], const int (&b_row)[T::NI],
-                                      bool active, f32x16 (&acc)[T::MI][T::NI]) {
+                                      bool active, int rot_, f32x16 (&acc)[T::MI][T::NI]) {
     const int tid = threadIdx.x, lane = tid & 63;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
     lds = lds_; zeros = reinterpret_cast<const char*>(zeros_); K = K_;
     if (K <= 0) return;
     nfull = K / T::BK;
     nslabs = (K + T::BK - 1) / T::BK;
+    rot = rot_ % nslabs;
 #pragma unroll
     for (int i = 0; i < T::MI; ++i)
 #pragma unroll
@@ -429,9 +433,9 @@ __global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __
   const int e = threadIdx.x;
   if (e < 64) rt.zeros[e] = 0u;
   int begin = 0, end = 0, nt = 0;
-  if (e < E) {
-    begin = min(max(offsets[e], 0), P);
-    end = min(max(offsets[e + 1], begin), P);
+  if (e < E) {                                       // offsets == null: one segment holding all P rows
+    begin = offsets ? min(max(offsets[e], 0), P) : 0;
+    end = offsets ? min(max(offsets[e + 1], begin), P) : P;
     nt = (end - begin + bm - 1) / bm;
   }
   scan[e] = nt;
@@ -472,7 +476,7 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[T::MI][T::NI]) {
 // ============================================================================================
 // Row-grouped kernels
 // ============================================================================================
-enum { kGateUp = 0, kDown = 1, kDAct = 2, kDX = 3 };
+enum { kGateUp = 0, kDown = 1, kDAct = 2, kDX = 3, kRouterFwd = 4, kRouterDx = 5 };
 
 struct RowArgs {
   const bf16_t* a;         // activation operand [P, lda]
@@ -487,13 +491,16 @@ struct RowArgs {
   int P;
   RowTiles rt;
   int n_tiles_n;
-  bf16_t* out0;            // kGateUp: G (may be null)   kDown/kDX: output     kDAct: [dG | dU]
+  bf16_t* out0;            // kGateUp: G (may be null)   kDown/kDX/kRouterDx: output     kDAct: [dG | dU]
   bf16_t* out1;            // kGateUp: U (may be null)
   bf16_t* out2;            // kGateUp: act (may be null)
   long ldo;
+  float* out_f32;          // kRouterFwd: fp32 output
+  int accumulate;          // kRouterDx: add to what out0 holds
   const bf16_t* g;         // kDAct: saved pre-activations
   const bf16_t* u;
   const bf16_t* zeros;     // at least 16 zero bytes (source of out-of-range reduction indices)
+  int rot_q4;
   unsigned long long* clock;   // null, or where the first workgroup records the clock it ran at
 };
 
@@ -508,9 +515,11 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   if (v < 0) return;
   ClockStamp stamp(p.clock);
   const int mt = v / p.n_tiles_n, nt = v % p.n_tiles_n;
+  // workgroup b is the (b / 8)-th one its XCD receives; rot_q4 is slabs of rotation per such position, in 1/16
+  const int tile_rot = static_cast<int>((static_cast<long>(blockIdx.x / kXcds) * p.rot_q4) >> 4);
   const int e = p.rt.expert[mt];
   const int row0 = p.rt.row0[mt];
-  const int row_end = min(p.offsets[e + 1], p.P);
+  const int row_end = p.offsets ? min(p.offsets[e + 1], p.P) : p.P;
   const int rows = min(BM, row_end - row0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / T::WGN, wn = wave % T::WGN;
@@ -546,7 +555,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.half[1] = p.w1 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.valid[0] = opB.valid[1] = ncols;
-    { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc);
+    { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc);
     }
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
@@ -585,16 +594,16 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     for (int i = 0; i < NI; ++i) b_row[i] = wn * WN + i * 32;
     opB.valid[0] = min(ncols, BN / 2);
     opB.valid[1] = max(ncols - BN / 2, 0);
-    if constexpr (KIND == kDown) {
-      // yp = act * Wd[e]^T : weight rows are output columns, reduction contiguous
+    if constexpr (KIND == kDown || KIND == kRouterFwd) {
+      // yp = act * Wd[e]^T (logits = x * Wr^T): weight rows are output columns, reduction contiguous
       opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
       opB.half[1] = opB.half[0] + (BN / 2) * p.ldw;
-      { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
-    } else if constexpr (KIND == kDAct) {
-      // dA = dyp * Wd[e] : weight is [K = d, N = f], reduction strided
+      { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc); }
+    } else if constexpr (KIND == kDAct || KIND == kRouterDx) {
+      // dA = dyp * Wd[e] (dx = dz * Wr): weight is [K, N], reduction strided
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
       opB.half[1] = opB.half[0] + BN / 2;
-      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
+      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc); }
     } else {
       // dxp = dG * Wg[e] + dU * Wu[e] : two reduction segments over the columns of [dG | dU]
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
@@ -605,7 +614,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       opsB[1] = opB;
       opsB[1].half[0] = p.w1 + e * p.w_expert_stride + n0;
       opsB[1].half[1] = opsB[1].half[0] + BN / 2;
-      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 2, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
+      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 2, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc); }
     }
 
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
@@ -638,6 +647,19 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
               const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
               *reinterpret_cast<uint4*>(p.out0 + o) = pack8(dg);
               *reinterpret_cast<uint4*>(p.out0 + o + p.N) = pack8(du);
+            } else if constexpr (KIND == kRouterFwd) {
+              float* o = p.out_f32 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+              *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+              *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            } else if constexpr (KIND == kRouterDx) {
+              bf16_t* o = p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+              if (p.accumulate) {
+                float old[8];
+                unpack8(*reinterpret_cast<const uint4*>(o), old);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v[q] += old[q];
+              }
+              *reinterpret_cast<uint4*>(o) = pack8(v);
             } else {
               *reinterpret_cast<uint4*>(p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl) = pack8(v);
             }
@@ -680,9 +702,9 @@ __global__ __launch_bounds__(1024) void build_wgrad_items_kernel(const int32_t* 
   __shared__ int32_t scan_split[kMaxExperts];
   const int e = threadIdx.x;
   int begin = 0, c = -1;
-  if (e < E) {
-    begin = min(max(offsets[e], 0), P);
-    c = min(max(offsets[e + 1], begin), P) - begin;
+  if (e < E) {                                       // offsets == null: one segment holding all P rows
+    begin = offsets ? min(max(offsets[e], 0), P) : 0;
+    c = (offsets ? min(max(offsets[e + 1], begin), P) : P) - begin;
   }
   cnt[e] = c;
   __syncthreads();
@@ -712,7 +734,7 @@ __global__ __launch_bounds__(1024) void build_wgrad_items_kernel(const int32_t* 
   }
   if (e < E) {
     const int first = scan_items[e] - my_n, slot0 = scan_slots[e] - (split ? my_n : 0), sidx = scan_split[e] - split;
-    const int row0 = min(max(offsets[my_e], 0), P);
+    const int row0 = offsets ? min(max(offsets[my_e], 0), P) : 0;
     // the host sizes the lists for the worst case; offsets that are not a monotone scan ending at P cannot overflow them
     const bool fits = slot0 + my_n <= it.max_slots && sidx < it.max_split;
     for (int j = 0; j < my_n && first + j < it.max_items; ++j) {
@@ -782,7 +804,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   opB.half[1] = opB.half[0] + BN / 2;
   opB.valid[0] = min(ncols, BN / 2);
   opB.valid[1] = max(ncols - BN / 2, 0);
-  { MainLoop<T, true, true> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, acc); }
+  { MainLoop<T, true, true> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, 0, acc); }
 
   float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
   constexpr int LPR = WN / 8;
@@ -938,7 +960,7 @@ static unsigned padded_grid(int tiles) { return static_cast<unsigned>(ceil_div(t
 
 template <int KIND, class T>
 static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
-  static const char* const names[4] = {"ffn_gate_up", "ffn_down", "ffn_dact", "ffn_dx"};
+  static const char* const names[6] = {"ffn_gate_up", "ffn_down", "ffn_dact", "ffn_dx", "router_logits", "router_dx"};
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&row_grouped_kernel<KIND, T>),
@@ -946,7 +968,8 @@ static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
     attr_set = true;
   }
   p.n_tiles_n = ceil_div(p.N, KIND == kGateUp ? T::BN / 2 : T::BN);
-  p.clock = prof_clock_slot(KIND);
+  { const char* rs = getenv("MOE_GEMM_ROT"); p.rot_q4 = rs ? atoi(rs) : 0; }
+  p.clock = KIND < 4 ? prof_clock_slot(KIND) : nullptr;
   const unsigned grid = padded_grid((ceil_div(P, T::BM) + E) * p.n_tiles_n);
   MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);
 }
@@ -965,15 +988,16 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
     attr_set = true;
   }
-  p.clock = prof_clock_slot(4 + WHICH);
+  p.clock = WHICH < 2 ? prof_clock_slot(4 + WHICH) : nullptr;
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
   const unsigned grid = padded_grid(p.tiles_m * p.tiles_n * p.items.max_items);
-  MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : "wgrad_gate_up", (wgrad_kernel<WHICH, T>), dim3(grid), dim3(T::kThreads),
-             T::kLdsBytes, s, p);
+  MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T>), dim3(grid),
+             dim3(T::kThreads), T::kLdsBytes, s, p);
   const long rblocks = (static_cast<long>(p.M) * p.N + 2047) / 2048;
   const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 256L)), static_cast<unsigned>(p.items.max_split));
-  MOE_LAUNCH(WHICH == 0 ? "wgrad_down_reduce" : "wgrad_gate_up_reduce", wgrad_reduce_kernel, rgrid, dim3(256), 0, s, p);
+  MOE_LAUNCH(WHICH == 0 ? "wgrad_down_reduce" : WHICH == 1 ? "wgrad_gate_up_reduce" : "wgrad_router_reduce", wgrad_reduce_kernel, rgrid,
+             dim3(256), 0, s, p);
 }
 
 template <int WHICH>
@@ -1057,6 +1081,118 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_gate); p.out1 = static_cast<bf16_t*>(a.dw_up); p.m_split = a.f;
     launch_wgrad<1>(p, a.stream);
+  }
+}
+
+// ============================================================================================
+// Router linear (the gate that produces the logits) and its backward, on the same skeleton:
+//   logits[T, E] (fp32)  = x[T, d] * Wr[E, d]^T          one segment of T rows, fp32 epilogue
+//   dx[T, d]   (+)=  bf16(dz)[T, E] * Wr[E, d]           reduction over E, optional read-modify-write
+//   dWr[E, d]       =  bf16(dz)[T, E]^T * x[T, d]         reduction over the T rows, chunked like the others
+// The fp32 logit gradient is rounded to bf16 once for the two backward products (bf16 operands,
+// fp32 accumulation, like every other product here).
+// ============================================================================================
+__global__ __launch_bounds__(256) void cast_f32_bf16_kernel(const float* __restrict__ in, bf16_t* __restrict__ out, long n8) {
+  const long i = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= n8) return;
+  float v[8];
+  read8(in + i * 8, v);
+  *reinterpret_cast<uint4*>(out + i * 8) = pack8(v);
+}
+
+struct RouterWs { size_t tiles_count, zeros, tiles_expert, tiles_row0, dz, items, partial, total; };
+static RouterWs router_ws(int T, int d, int E, bool bwd) {
+  RouterWs w{};
+  size_t off = 0;
+  w.tiles_count = off; off += 256;
+  w.zeros = off; off += 256;
+  const size_t t = align_up(static_cast<size_t>(max_row_tiles(T, 1)) * sizeof(int32_t), 256);
+  w.tiles_expert = off; off += t;
+  w.tiles_row0 = off; off += t;
+  w.dz = off; w.items = off; w.partial = off;
+  if (bwd) {
+    off += align_up(static_cast<size_t>(T) * E * 2, 256);
+    w.items = off;
+    const size_t it = align_up(static_cast<size_t>(wgrad_max_items(T, 1)) * sizeof(int32_t), 256);
+    const size_t sp = align_up(static_cast<size_t>(wgrad_max_split(T, 1)) * sizeof(int32_t), 256);
+    off += 256 + 4 * it + 3 * sp;
+    w.partial = off;
+    off += align_up(static_cast<size_t>(wgrad_max_slots(T)) * E * d * sizeof(float), 256);
+  }
+  w.total = off + 256;
+  return w;
+}
+size_t router_fwd_ws_bytes_bf16(int T, int d, int E) { return router_ws(T, d, E, false).total; }
+size_t router_bwd_ws_bytes_bf16(int T, int d, int E) { return router_ws(T, d, E, true).total; }
+
+static RowTiles router_tiles_at(void* ws, const RouterWs& w, int T) {
+  char* b = static_cast<char*>(ws);
+  RowTiles rt;
+  rt.max_tiles = max_row_tiles(T, 1);
+  rt.count = reinterpret_cast<int32_t*>(b + w.tiles_count);
+  rt.zeros = reinterpret_cast<uint32_t*>(b + w.zeros);
+  rt.expert = reinterpret_cast<int32_t*>(b + w.tiles_expert);
+  rt.row0 = reinterpret_cast<int32_t*>(b + w.tiles_row0);
+  return rt;
+}
+
+void router_fwd_bf16(const RouterFwdArgs& a) {
+  const RouterWs w = router_ws(a.T, a.d, a.E, false);
+  const RowTiles rt = router_tiles_at(a.ws, w, a.T);
+  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, static_cast<const int32_t*>(nullptr), 1, a.T,
+             row_bm(), rt);
+  RowArgs p{};
+  p.a = static_cast<const bf16_t*>(a.x); p.lda = a.d;
+  p.w0 = static_cast<const bf16_t*>(a.w_router); p.w_expert_stride = 0; p.ldw = a.d;
+  p.K = a.d; p.N = a.E; p.offsets = nullptr; p.P = a.T; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+  p.out_f32 = a.logits; p.ldo = a.E;
+  launch_row<kRouterFwd>(p, a.T, 1, a.stream);
+}
+
+void router_bwd_bf16(const RouterBwdArgs& a) {
+  const RouterWs w = router_ws(a.T, a.d, a.E, true);
+  const RowTiles rt = router_tiles_at(a.ws, w, a.T);
+  char* base = static_cast<char*>(a.ws);
+  bf16_t* dz = reinterpret_cast<bf16_t*>(base + w.dz);
+  const long n8 = static_cast<long>(a.T) * a.E / 8;
+  MOE_LAUNCH("router_cast_dz", cast_f32_bf16_kernel, dim3(static_cast<unsigned>((n8 + 255) / 256)), dim3(256), 0, a.stream, a.dlogits, dz, n8);
+  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, static_cast<const int32_t*>(nullptr), 1, a.T,
+             row_bm(), rt);
+  {  // dx (+)= dz * Wr
+    RowArgs p{};
+    p.a = dz; p.lda = a.E;
+    p.w0 = static_cast<const bf16_t*>(a.w_router); p.w_expert_stride = 0; p.ldw = a.d;
+    p.K = a.E; p.N = a.d; p.offsets = nullptr; p.P = a.T; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+    p.out0 = static_cast<bf16_t*>(a.dx); p.ldo = a.d; p.accumulate = a.accumulate;
+    launch_row<kRouterDx>(p, a.T, 1, a.stream);
+  }
+  {  // dWr = dz^T x
+    WgradItems items;
+    {
+      char* b = base + w.items;
+      items.max_items = wgrad_max_items(a.T, 1);
+      items.max_split = wgrad_max_split(a.T, 1);
+      items.max_slots = wgrad_max_slots(a.T);
+      const size_t li = align_up(static_cast<size_t>(items.max_items) * sizeof(int32_t), 256);
+      const size_t ls = align_up(static_cast<size_t>(items.max_split) * sizeof(int32_t), 256);
+      items.count = reinterpret_cast<int32_t*>(b); b += 256;
+      items.expert = reinterpret_cast<int32_t*>(b); b += li;
+      items.k0 = reinterpret_cast<int32_t*>(b); b += li;
+      items.k1 = reinterpret_cast<int32_t*>(b); b += li;
+      items.slot = reinterpret_cast<int32_t*>(b); b += li;
+      items.split_expert = reinterpret_cast<int32_t*>(b); b += ls;
+      items.split_slot0 = reinterpret_cast<int32_t*>(b); b += ls;
+      items.split_n = reinterpret_cast<int32_t*>(b);
+    }
+    MOE_LAUNCH("build_wgrad_items", build_wgrad_items_kernel, dim3(1), dim3(1024), 0, a.stream, static_cast<const int32_t*>(nullptr), 1, a.T,
+               wgrad_chunk_rows(a.T), items);
+    WgradArgs p{};
+    p.lhs = dz; p.ld_lhs = a.E; p.M = a.E;
+    p.rhs = static_cast<const bf16_t*>(a.x); p.ld_rhs = a.d; p.N = a.d;
+    p.E = 1; p.P = a.T; p.items = items; p.partial = reinterpret_cast<float*>(base + w.partial);
+    p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+    p.out0 = static_cast<bf16_t*>(a.dw_router); p.out1 = p.out0; p.m_split = a.E;
+    launch_wgrad<2>(p, a.stream);
   }
 }
 

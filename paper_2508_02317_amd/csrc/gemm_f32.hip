@@ -169,4 +169,47 @@ void ffn_bwd_f32(const FfnBwdArgs& a) {
                      static_cast<float*>(a.dw_up));
 }
 
+// ---- router linear, fp32 element type: one thread per output, sequential FMA ----------------------
+__global__ __launch_bounds__(kF32Threads) void f32_router_logits_kernel(const float* __restrict__ x, const float* __restrict__ wr,
+                                                                        int T, int d, int E, float* __restrict__ logits) {
+  const long i = static_cast<long>(blockIdx.x) * kF32Threads + threadIdx.x;
+  if (i >= static_cast<long>(T) * E) return;
+  const int t = static_cast<int>(i / E), e = static_cast<int>(i % E);
+  const float* xr = x + static_cast<long>(t) * d;
+  const float* w = wr + static_cast<long>(e) * d;
+  float acc = 0.0f;
+  for (int c = 0; c < d; ++c) acc = fmaf(xr[c], w[c], acc);
+  logits[i] = acc;
+}
+__global__ __launch_bounds__(kF32Threads) void f32_router_dx_kernel(const float* __restrict__ dz, const float* __restrict__ wr,
+                                                                    int T, int d, int E, int accumulate, float* __restrict__ dx) {
+  const long i = static_cast<long>(blockIdx.x) * kF32Threads + threadIdx.x;
+  if (i >= static_cast<long>(T) * d) return;
+  const int t = static_cast<int>(i / d), c = static_cast<int>(i % d);
+  float acc = 0.0f;
+  for (int e = 0; e < E; ++e) acc = fmaf(dz[static_cast<long>(t) * E + e], wr[static_cast<long>(e) * d + c], acc);
+  dx[i] = accumulate ? dx[i] + acc : acc;
+}
+__global__ __launch_bounds__(kF32Threads) void f32_router_dw_kernel(const float* __restrict__ dz, const float* __restrict__ x,
+                                                                    int T, int d, int E, float* __restrict__ dwr) {
+  const long i = static_cast<long>(blockIdx.x) * kF32Threads + threadIdx.x;
+  if (i >= static_cast<long>(E) * d) return;
+  const int e = static_cast<int>(i / d), c = static_cast<int>(i % d);
+  float acc = 0.0f;
+  for (int t = 0; t < T; ++t) acc = fmaf(dz[static_cast<long>(t) * E + e], x[static_cast<long>(t) * d + c], acc);
+  dwr[i] = acc;
+}
+
+void router_fwd_f32(const RouterFwdArgs& a) {
+  MOE_LAUNCH("f32_router_logits", f32_router_logits_kernel, dim3(blocks_for(static_cast<size_t>(a.T) * a.E)), dim3(kF32Threads), 0,
+             a.stream, static_cast<const float*>(a.x), static_cast<const float*>(a.w_router), a.T, a.d, a.E, a.logits);
+}
+void router_bwd_f32(const RouterBwdArgs& a) {
+  if (a.T > 0)
+    MOE_LAUNCH("f32_router_dx", f32_router_dx_kernel, dim3(blocks_for(static_cast<size_t>(a.T) * a.d)), dim3(kF32Threads), 0, a.stream,
+               a.dlogits, static_cast<const float*>(a.w_router), a.T, a.d, a.E, a.accumulate, static_cast<float*>(a.dx));
+  MOE_LAUNCH("f32_router_dw", f32_router_dw_kernel, dim3(blocks_for(static_cast<size_t>(a.E) * a.d)), dim3(kF32Threads), 0, a.stream,
+             a.dlogits, static_cast<const float*>(a.x), a.T, a.d, a.E, static_cast<float*>(a.dw_router));
+}
+
 }  // namespace moe

@@ -121,4 +121,28 @@ size_t ffn_bwd_ws_bytes_f32(int P, int d, int f, int E, int have_saved);
 void ffn_fwd_f32(const FfnFwdArgs& a);
 void ffn_bwd_f32(const FfnBwdArgs& a);
 
+// ---- router linear (gemm_bf16.hip: bf16 MFMA; gemm_f32.hip: fp32 reference-speed kernels) --------
+struct RouterFwdArgs {
+  const void *x, *w_router;    // [T, d], [E, d]
+  int T, d, E;
+  float* logits;               // [T, E]
+  void* ws;
+  hipStream_t stream;
+};
+struct RouterBwdArgs {
+  const float* dlogits;        // [T, E]
+  const void *x, *w_router;
+  int T, d, E;
+  int accumulate;              // add to dx instead of overwriting it
+  void *dx, *dw_router;        // [T, d], [E, d]
+  void* ws;
+  hipStream_t stream;
+};
+size_t router_fwd_ws_bytes_bf16(int T, int d, int E);
+size_t router_bwd_ws_bytes_bf16(int T, int d, int E);
+void router_fwd_bf16(const RouterFwdArgs& a);
+void router_bwd_bf16(const RouterBwdArgs& a);
+void router_fwd_f32(const RouterFwdArgs& a);
+void router_bwd_f32(const RouterBwdArgs& a);
+
 }  // namespace moe

@@ -21,8 +21,12 @@ class MoELayer:
     """
 
     def __init__(self, T, d, E, k, f, dtype, w_gate, w_up, w_down, renorm=1, prerouted=False,
-                 save_gu=True, device="cuda"):
+                 save_gu=True, device="cuda", w_router=None):
+        """w_router [E, d], if given, makes the layer start from hidden states: forward() computes the logits
+        itself and backward() also returns the router's weight gradient and adds the router term to dx."""
         assert not prerouted or k == 1
+        assert w_router is None or not prerouted
+        self.w_router = w_router
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
         self.P = T * k
         self.dtype, self.renorm, self.prerouted, self.save_gu = dtype, renorm, prerouted, save_gu
@@ -45,7 +49,11 @@ class MoELayer:
         self.dw_gate, self.dw_up, self.dw_down = torch.empty_like(w_gate), torch.empty_like(w_up), torch.empty_like(w_down)
         self.dx = el(T, d)
         self.dlogits = None if prerouted else f32(T, E)
+        self.logits = f32(T, E) if w_router is not None else None
+        self.dw_router = torch.empty_like(w_router) if w_router is not None else None
         ws_bytes = max(
+            L.lib.moe_router_logits_workspace_bytes(code, T, d, E) if w_router is not None else 0,
+            L.lib.moe_router_bwd_workspace_bytes(code, T, d, E) if w_router is not None else 0,
             L.lib.moe_route_topk_workspace_bytes(T, E, k),
             L.lib.moe_expert_offsets_workspace_bytes(P, E),
             L.lib.moe_permute_workspace_bytes(T, E, k),
@@ -55,11 +63,14 @@ class MoELayer:
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def forward(self, x, logits=None, topk_idx=None, topk_w=None):
+        self.x = x
         if self.prerouted:
             self.topk_idx.copy_(topk_idx.view(self.T, 1))
             self.topk_w.copy_(topk_w.view(self.T, 1))
             L.moe_expert_offsets(self.topk_idx, self.E, out=(self.counts, self.offsets), ws=self.ws)
         else:
+            if self.w_router is not None:
+                logits = L.moe_router_logits(x, self.w_router, out=self.logits, ws=self.ws)
             L.moe_route_topk(logits, self.k, self.renorm,
                              out=(self.topk_idx, self.topk_w, self.counts, self.offsets), ws=self.ws)
         L.moe_permute(x, self.topk_idx, self.offsets, self.E,
@@ -76,5 +87,9 @@ class MoELayer:
                                       out=(self.dxp, self.dw_gate, self.dw_up, self.dw_down), ws=self.ws)
         L.moe_unpermute_combine_fwd(self.dxp, None, self.row_of_pair, self.T, self.k, out=self.dx)
         if not self.prerouted:
+            if self.w_router is not None:
+                logits = self.logits
             L.moe_route_topk_bwd(self.dw, self.topk_w, self.topk_idx, logits, self.E, self.renorm, out=self.dlogits)
+            if self.w_router is not None:
+                L.moe_router_bwd(self.dlogits, self.x, self.w_router, dx=self.dx, out_dw=self.dw_router, ws=self.ws)
         return self.dx, self.dw_gate, self.dw_up, self.dw_down, self.dlogits

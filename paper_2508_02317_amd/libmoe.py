@@ -26,6 +26,7 @@ EXPORTS = [
     "moe_grouped_gemm_swiglu_fwd_workspace_bytes", "moe_grouped_gemm_swiglu_fwd",
     "moe_grouped_gemm_swiglu_bwd_workspace_bytes", "moe_grouped_gemm_swiglu_bwd",
     "moe_unpermute_combine_fwd", "moe_unpermute_combine_bwd",
+    "moe_router_logits_workspace_bytes", "moe_router_logits", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
     "moe_profile_enable", "moe_profile_report", "moe_profile_shader_clock",
 ]
 
@@ -73,6 +74,14 @@ def _load():
     lib.moe_unpermute_combine_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.moe_unpermute_combine_bwd.restype = ctypes.c_int32
     lib.moe_unpermute_combine_bwd.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.moe_router_logits_workspace_bytes.restype = sz
+    lib.moe_router_logits_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.moe_router_logits.restype = ctypes.c_int32
+    lib.moe_router_logits.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.moe_router_bwd_workspace_bytes.restype = sz
+    lib.moe_router_bwd_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.moe_router_bwd.restype = ctypes.c_int32
+    lib.moe_router_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.moe_profile_enable.restype = ctypes.c_int32
     lib.moe_profile_enable.argtypes = [i32]
     lib.moe_profile_shader_clock.restype = ctypes.c_int32
@@ -269,3 +278,36 @@ def moe_unpermute_combine_bwd(dy, yp, topk_w, row_of_pair, out=None):
     _check(lib.moe_unpermute_combine_bwd(_ptr(dy), _ptr(yp), _dtype_code(yp), T, d, k, _ptr(topk_w), _ptr(row_of_pair),
                                          _ptr(dyp), _ptr(dw), _stream()))
     return dyp, dw
+
+
+def moe_router_logits(x, w_router, out=None, ws=None):
+    """-> logits [T,E] f32 = x [T,d] @ w_router [E,d]^T."""
+    _need(x, None, "x"); _need(w_router, x.dtype, "w_router")
+    T, d = x.shape
+    E = w_router.shape[0]
+    dt = _dtype_code(x)
+    if out is None:
+        out = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    ws, n = _ws(lib.moe_router_logits_workspace_bytes(dt, T, d, E), ws, x.device)
+    _check(lib.moe_router_logits(_ptr(x), _ptr(w_router), dt, T, d, E, _ptr(out), _ptr(ws), n, _stream()))
+    return out
+
+
+def moe_router_bwd(dlogits, x, w_router, dx=None, out_dw=None, ws=None):
+    """-> dx [T,d] (dx given: the router term is added to it in place), dw_router [E,d]."""
+    _need(dlogits, torch.float32, "dlogits"); _need(x, None, "x"); _need(w_router, x.dtype, "w_router")
+    T, d = x.shape
+    E = w_router.shape[0]
+    dt = _dtype_code(x)
+    accumulate = dx is not None
+    if dx is None:
+        dx = torch.empty_like(x)
+    else:
+        _need(dx, x.dtype, "dx")
+    if out_dw is None:
+        out_dw = torch.empty_like(w_router)
+    ws, n = _ws(lib.moe_router_bwd_workspace_bytes(dt, T, d, E), ws, x.device)
+    _check(lib.moe_router_bwd(_ptr(dlogits), _ptr(x), _ptr(w_router), dt, T, d, E, int(accumulate), _ptr(dx), _ptr(out_dw),
+                              _ptr(ws), n, _stream()))
+    return dx, out_dw
+

@@ -1,0 +1,117 @@
+"""GPU parity of the router linear and of the whole block (hidden states in, hidden-state gradient out)
+against the fp64 oracle.  Routing decisions are compared on the logits the GPU produced (the oracle routes
+on that same fp32 array), so that a near-tie cannot turn rounding into an index mismatch; the accuracy of
+the logits themselves is a separate float check."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import moe_oracle as O
+from paper_2508_02317_amd.inputs import quantise
+from tests.util import TOL, assert_close, q, rel_err, to_dev, to_np, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True, file=sys.stderr)
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2508_02317_amd import libmoe
+    return libmoe
+
+
+ROUTER_CASES = [
+    # T, d, E, dtype
+    (256, 128, 8, "f32"),
+    (1000, 512, 128, "bf16"),        # several row tiles, ragged last one
+    (4100, 264, 16, "bf16"),         # reduction over tokens longer than four chunks; d not a multiple of the tile
+    (77, 2048, 128, "bf16"),
+    (5, 64, 8, "bf16"),
+    (300, 72, 40, "f32"),
+]
+
+
+@pytest.mark.parametrize("T,d,E,dt", ROUTER_CASES)
+def test_router_linear_fwd_bwd(L, T, d, E, dt):
+    say("router T=%d d=%d E=%d %s" % (T, d, E, dt))
+    r = np.random.default_rng(T + d + E)
+    X = q(r.standard_normal((T, d)), dt)
+    Wr = q(r.standard_normal((E, d)) * 0.05, dt)
+    tx, tw = to_dev(X, dt), to_dev(Wr, dt)
+    logits = L.moe_router_logits(tx, tw)
+    # fp32 output of an fp32-accumulated product of exactly representable inputs
+    assert_close(to_np(logits), O.router_logits(X, Wr), dt, "logits", tol=1e-5)
+    # backward with a dense upstream gradient and with a k-sparse one (what the routing backward produces)
+    for kind in ("dense", "sparse"):
+        dz = r.standard_normal((T, E)).astype(np.float32)
+        if kind == "sparse":
+            keep = np.argsort(r.random((T, E)), axis=1)[:, : min(4, E)]
+            m = np.zeros((T, E), dtype=bool)
+            np.put_along_axis(m, keep, True, axis=1)
+            dz = np.where(m, dz, 0.0).astype(np.float32)
+        # the bf16 path rounds dz once before its two products: the oracle gets the same rounded values
+        dz_seen = quantise(dz, dt) if dt == "bf16" else dz
+        rdX, rdW = O.router_bwd(dz_seen, X, Wr)
+        dx, dw = L.moe_router_bwd(to_dev(dz), tx, tw)
+        assert_close(to_np(dx), rdX, dt, "dx_router (%s)" % kind)
+        assert_close(to_np(dw), rdW, dt, "dw_router (%s)" % kind)
+        # accumulate mode: dx already holds the expert-path gradient
+        base = q(r.standard_normal((T, d)), dt)
+        acc = to_dev(base, dt)
+        dx2, _ = L.moe_router_bwd(to_dev(dz), tx, tw, dx=acc)
+        assert dx2.data_ptr() == acc.data_ptr()
+        assert_close(to_np(dx2), base.astype(np.float64) + rdX, dt, "dx accumulate (%s)" % kind)
+    # deterministic
+    a = L.moe_router_bwd(to_dev(dz), tx, tw)
+    b = L.moe_router_bwd(to_dev(dz), tx, tw)
+    assert np.array_equal(to_np(a[0]), to_np(b[0])) and np.array_equal(to_np(a[1]), to_np(b[1]))
+
+
+def test_router_bwd_without_rows_writes_zero_weight_gradient(L):
+    import torch
+    for dt in (torch.bfloat16, torch.float32):
+        E, d = 16, 64
+        w = torch.randn(E, d, device="cuda").to(dt)
+        x = torch.empty((0, d), dtype=dt, device="cuda")
+        dz = torch.empty((0, E), dtype=torch.float32, device="cuda")
+        dw = torch.full_like(w, 3.0)
+        L.moe_router_bwd(dz, x, w, out_dw=dw)
+        torch.cuda.synchronize()
+        assert not dw.any()
+        assert L.moe_router_logits(x, w).shape == (0, E)
+
+
+@pytest.mark.parametrize("T,d,E,k,f,dt,renorm", [(300, 128, 16, 2, 96, "bf16", 1), (256, 64, 8, 3, 64, "f32", 0),
+                                                 (1500, 256, 128, 8, 64, "bf16", 1)])
+def test_whole_block_from_hidden_states(L, T, d, E, k, f, dt, renorm):
+    """x -> router linear -> route -> permute -> experts -> combine, and all the way back to dx, dW_router
+    and the expert weight gradients, against the oracle's block backward."""
+    from paper_2508_02317_amd.layer import MoELayer
+    say("block T=%d d=%d E=%d k=%d f=%d %s renorm=%d" % (T, d, E, k, f, dt, renorm))
+    r = np.random.default_rng(T + E + k)
+    X = q(r.standard_normal((T, d)), dt)
+    Wr = q(r.standard_normal((E, d)) * (1.0 / np.sqrt(d)), dt)
+    Wg, Wu = q(r.standard_normal((E, f, d)) * 0.05, dt), q(r.standard_normal((E, f, d)) * 0.05, dt)
+    Wd = q(r.standard_normal((E, d, f)) * 0.05, dt)
+    dY = q(r.standard_normal((T, d)), dt)
+    layer = MoELayer(T, d, E, k, f, torch_dtype(dt), to_dev(Wg, dt), to_dev(Wu, dt), to_dev(Wd, dt), renorm=renorm,
+                     w_router=to_dev(Wr, dt))
+    x, dy = to_dev(X, dt), to_dev(dY, dt)
+    layer.forward(x)
+    layer.backward(dy)
+    z = to_np(layer.logits)
+    assert_close(z, O.router_logits(X, Wr), dt, "logits", tol=1e-5)
+    fwd = O.moe_layer_fwd(X, z, Wg, Wu, Wd, k, renorm)              # routed on the GPU's own logits
+    assert np.array_equal(to_np(layer.topk_idx), fwd["topk_idx"])
+    assert_close(to_np(layer.y), fwd["Y"], dt, "Y")
+    blk = O.moe_block_bwd(fwd, dY, z, X, Wr, Wg, Wu, Wd, renorm)
+    assert_close(to_np(layer.dlogits), blk["dlogits"], dt, "dlogits", tol=max(TOL[dt], 1e-4))
+    assert_close(to_np(layer.dx), blk["dX"], dt, "dX (expert + router path)")
+    assert_close(to_np(layer.dw_router), blk["dWr"], dt, "dW_router")
+    assert_close(to_np(layer.dw_gate), blk["dWg"], dt, "dW_gate")
+    assert_close(to_np(layer.dw_down), blk["dWd"], dt, "dW_down")
+    say("  router share of |dX|: %.3f" % (np.abs(blk["dX_router"]).max() / np.abs(blk["dX"]).max()))

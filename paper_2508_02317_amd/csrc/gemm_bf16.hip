@@ -266,12 +266,9 @@ struct MainLoop {
   char* lds;
   const char* zeros;
   int nslabs, nfull, K, wave;
-  int rot;                   // the reduction starts at slab `rot` and wraps around
 
-  __device__ __forceinline__ void issue(int step, int stage) {
+  __device__ __forceinline__ void issue(int slab, int stage) {
     char* st = lds + stage * T::kStageBytes;
-    int slab = step + rot;
-    if (slab >= nslabs) slab -= nslabs;
     if (slab < nfull) {
       da.issue(slab, st, wave);
       db.issue(slab, st + T::kABytes, wave);
@@ -341,14 +338,13 @@ struct MainLoop {
 
   __device__ __forceinline__ void run(const Operand* opA, const Operand* opB, int nseg, int K_, char* lds_,
                                       const bf16_t* zeros_, const int (&a_row)[T::MI], const int (&b_row)[T::NI],
-                                      bool active, int rot_, f32x16 (&acc)[T::MI][T::NI]) {
+                                      bool active, f32x16 (&acc)[T::MI][T::NI]) {
     const int tid = threadIdx.x, lane = tid & 63;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
     lds = lds_; zeros = reinterpret_cast<const char*>(zeros_); K = K_;
     if (K <= 0) return;
     nfull = K / T::BK;
     nslabs = (K + T::BK - 1) / T::BK;
-    rot = rot_ % nslabs;
 #pragma unroll
     for (int i = 0; i < T::MI; ++i)
 #pragma unroll
@@ -500,7 +496,6 @@ struct RowArgs {
   const bf16_t* g;         // kDAct: saved pre-activations
   const bf16_t* u;
   const bf16_t* zeros;     // at least 16 zero bytes (source of out-of-range reduction indices)
-  int rot_q4;
   unsigned long long* clock;   // null, or where the first workgroup records the clock it ran at
 };
 
@@ -515,8 +510,6 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   if (v < 0) return;
   ClockStamp stamp(p.clock);
   const int mt = v / p.n_tiles_n, nt = v % p.n_tiles_n;
-  // workgroup b is the (b / 8)-th one its XCD receives; rot_q4 is slabs of rotation per such position, in 1/16
-  const int tile_rot = static_cast<int>((static_cast<long>(blockIdx.x / kXcds) * p.rot_q4) >> 4);
   const int e = p.rt.expert[mt];
   const int row0 = p.rt.row0[mt];
   const int row_end = p.offsets ? min(p.offsets[e + 1], p.P) : p.P;
@@ -555,7 +548,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.half[1] = p.w1 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.valid[0] = opB.valid[1] = ncols;
-    { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc);
+    { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc);
     }
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
@@ -598,12 +591,12 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       // yp = act * Wd[e]^T (logits = x * Wr^T): weight rows are output columns, reduction contiguous
       opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
       opB.half[1] = opB.half[0] + (BN / 2) * p.ldw;
-      { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc); }
+      { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     } else if constexpr (KIND == kDAct || KIND == kRouterDx) {
       // dA = dyp * Wd[e] (dx = dz * Wr): weight is [K, N], reduction strided
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
       opB.half[1] = opB.half[0] + BN / 2;
-      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc); }
+      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     } else {
       // dxp = dG * Wg[e] + dU * Wu[e] : two reduction segments over the columns of [dG | dU]
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
@@ -614,7 +607,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       opsB[1] = opB;
       opsB[1].half[0] = p.w1 + e * p.w_expert_stride + n0;
       opsB[1].half[1] = opsB[1].half[0] + BN / 2;
-      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 2, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, tile_rot, acc); }
+      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 2, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     }
 
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
@@ -804,7 +797,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   opB.half[1] = opB.half[0] + BN / 2;
   opB.valid[0] = min(ncols, BN / 2);
   opB.valid[1] = max(ncols - BN / 2, 0);
-  { MainLoop<T, true, true> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, 0, acc); }
+  { MainLoop<T, true, true> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, acc); }
 
   float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
   constexpr int LPR = WN / 8;
@@ -968,7 +961,6 @@ static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
     attr_set = true;
   }
   p.n_tiles_n = ceil_div(p.N, KIND == kGateUp ? T::BN / 2 : T::BN);
-  { const char* rs = getenv("MOE_GEMM_ROT"); p.rot_q4 = rs ? atoi(rs) : 0; }
   p.clock = KIND < 4 ? prof_clock_slot(KIND) : nullptr;
   const unsigned grid = padded_grid((ceil_div(P, T::BM) + E) * p.n_tiles_n);
   MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);

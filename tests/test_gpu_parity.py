@@ -369,3 +369,34 @@ def test_layer_small_config_full_size(L):
     bwd = O.moe_layer_bwd(fwd, inp["dY"], inp["logits"], inp["Wg"], inp["Wu"], inp["Wd"], cfg.renorm)
     layer = _run_layer(L, cfg, inp)
     _check_layer(layer, cfg, fwd, bwd)
+
+
+def test_dense_swiglu_mlp_is_the_one_expert_case(L):
+    """E = 1, k = 1: routing weight 1 for every token, one segment of all rows -- the layer is a plain dense
+    SwiGLU MLP, checked here against that closed form written with matrix products (no routing code)."""
+    from paper_2508_02317_amd.layer import MoELayer
+    T, d, f, dt = 700, 256, 384, "bf16"
+    r = np.random.default_rng(5)
+    X, dY = q(r.standard_normal((T, d)), dt), q(r.standard_normal((T, d)), dt)
+    Wg, Wu = q(r.standard_normal((1, f, d)) * 0.05, dt), q(r.standard_normal((1, f, d)) * 0.05, dt)
+    Wd = q(r.standard_normal((1, d, f)) * 0.05, dt)
+    logits = np.zeros((T, 1), dtype=np.float32)
+    layer = MoELayer(T, d, 1, 1, f, torch_dtype(dt), to_dev(Wg, dt), to_dev(Wu, dt), to_dev(Wd, dt))
+    tl = to_dev(logits)
+    layer.forward(to_dev(X, dt), logits=tl)
+    layer.backward(to_dev(dY, dt), logits=tl)
+    X64 = X.astype(np.float64)
+    G, U = X64 @ Wg[0].astype(np.float64).T, X64 @ Wu[0].astype(np.float64).T
+    sg = 1.0 / (1.0 + np.exp(-G))
+    A = G * sg * U
+    Y = A @ Wd[0].astype(np.float64).T
+    dA = dY.astype(np.float64) @ Wd[0].astype(np.float64)
+    dG, dU = dA * U * sg * (1.0 + G * (1.0 - sg)), dA * G * sg
+    dX = dG @ Wg[0].astype(np.float64) + dU @ Wu[0].astype(np.float64)
+    assert np.array_equal(to_np(layer.topk_w), np.ones((T, 1), dtype=np.float32))
+    assert np.array_equal(to_np(layer.xp), X)                      # the permutation is the identity
+    assert_close(to_np(layer.y), Y, dt, "Y")
+    assert_close(to_np(layer.dx), dX, dt, "dX")
+    assert_close(to_np(layer.dw_down)[0], dY.astype(np.float64).T @ A, dt, "dW_down")
+    assert_close(to_np(layer.dw_gate)[0], dG.T @ X64, dt, "dW_gate")
+    assert not to_np(layer.dlogits).any()                          # k = 1, renormalised: no gradient to the logit

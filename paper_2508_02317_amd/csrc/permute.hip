@@ -129,8 +129,10 @@ template <> struct Piece<MOE_F32> {
 };
 
 // ---- combine forward: y[t] = sum_j w[t,j] * yp[row(t,j)] ------------------------------------
-// One thread per 16-byte piece of y; the k source pieces are independent loads.
-template <int DT>
+// One thread per 16-byte piece of y.  The slot indices and weights of the token are fetched first, then
+// the source pieces of up to eight slots are all in flight together before the fp32 sum, which runs in
+// slot order (the same order on every run).  KB = slots per batch.
+template <int DT, int KB>
 __global__ __launch_bounds__(kMoverThreads) void combine_fwd_kernel(
     const uint4* __restrict__ yp, int T, int k, int n16, const float* __restrict__ topk_w,
     const int32_t* __restrict__ row_of_pair, uint4* __restrict__ y) {
@@ -145,30 +147,28 @@ __global__ __launch_bounds__(kMoverThreads) void combine_fwd_kernel(
   for (int i = 0; i < N; ++i) acc[i] = 0.0f;
   const int32_t* rows = row_of_pair + static_cast<size_t>(t) * k;
   const float* w = topk_w ? topk_w + static_cast<size_t>(t) * k : nullptr;
-  int j = 0;
-  for (; j + 4 <= k; j += 4) {
-    uint4 v[4];
-    float wj[4];
+  const int last = T * k - 1;
+  for (int j = 0; j < k; j += KB) {
+    int r[KB];
+    float wj[KB];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      v[u] = yp[static_cast<size_t>(min(max(rows[j + u], 0), T * k - 1)) * n16 + c];
-      wj[u] = w ? w[j + u] : 1.0f;
+    for (int u = 0; u < KB; ++u) {                       // slots beyond k repeat the last one with weight 0
+      const int ju = min(j + u, k - 1);
+      r[u] = min(max(rows[ju], 0), last);
+      wj[u] = j + u < k ? (w ? w[ju] : 1.0f) : 0.0f;
     }
+    uint4 v[KB];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      float f[N];
-      Piece<DT>::unpack(v[u], f);
+    for (int u = 0; u < KB; ++u) v[u] = yp[static_cast<size_t>(r[u]) * n16 + c];
 #pragma unroll
-      for (int i = 0; i < N; ++i) acc[i] = fmaf(wj[u], f[i], acc[i]);
+    for (int u = 0; u < KB; ++u) {
+      if (j + u < k) {
+        float f[N];
+        Piece<DT>::unpack(v[u], f);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fmaf(wj[u], f[i], acc[i]);
+      }
     }
-  }
-  for (; j < k; ++j) {
-    uint4 v = yp[static_cast<size_t>(min(max(rows[j], 0), T * k - 1)) * n16 + c];
-    float wj = w ? w[j] : 1.0f;
-    float f[N];
-    Piece<DT>::unpack(v, f);
-#pragma unroll
-    for (int i = 0; i < N; ++i) acc[i] = fmaf(wj, f[i], acc[i]);
   }
   y[piece] = Piece<DT>::pack(acc);
 }
@@ -288,12 +288,18 @@ extern "C" int32_t moe_unpermute_combine_fwd(const void* yp, int dtype, int T, i
   const int n16 = d * elem_size(dtype) / 16;
   const size_t total = static_cast<size_t>(T) * n16;
   const unsigned blocks = static_cast<unsigned>((total + kMoverThreads - 1) / kMoverThreads);
-  if (dtype == MOE_BF16)
-    MOE_LAUNCH("combine_fwd", combine_fwd_kernel<MOE_BF16>, dim3(blocks), dim3(kMoverThreads), 0, s,
-                       static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair, static_cast<uint4*>(y));
-  else
-    MOE_LAUNCH("combine_fwd", combine_fwd_kernel<MOE_F32>, dim3(blocks), dim3(kMoverThreads), 0, s,
-                       static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair, static_cast<uint4*>(y));
+  // eight slots in flight per thread when the token has that many, else four, two or one
+#define MOE_COMBINE_FWD(DT, KB) \
+  MOE_LAUNCH("combine_fwd", (combine_fwd_kernel<DT, KB>), dim3(blocks), dim3(kMoverThreads), 0, s, \
+             static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair, static_cast<uint4*>(y))
+  if (dtype == MOE_BF16) {
+    if (k >= 8) MOE_COMBINE_FWD(MOE_BF16, 8); else if (k >= 3) MOE_COMBINE_FWD(MOE_BF16, 4);
+    else if (k == 2) MOE_COMBINE_FWD(MOE_BF16, 2); else MOE_COMBINE_FWD(MOE_BF16, 1);
+  } else {
+    if (k >= 8) MOE_COMBINE_FWD(MOE_F32, 8); else if (k >= 3) MOE_COMBINE_FWD(MOE_F32, 4);
+    else if (k == 2) MOE_COMBINE_FWD(MOE_F32, 2); else MOE_COMBINE_FWD(MOE_F32, 1);
+  }
+#undef MOE_COMBINE_FWD
   return check_launch("moe_unpermute_combine_fwd");
 }
 

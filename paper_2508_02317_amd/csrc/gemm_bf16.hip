@@ -458,7 +458,6 @@ __device__ __forceinline__ int xcd_remap(int b, int total) {
   return (b / kXcds < per && v < total) ? v : -1;
 }
 
-
 template <class T>
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[T::MI][T::NI]) {
 #pragma unroll
@@ -496,10 +495,8 @@ struct RowArgs {
   const bf16_t* g;         // kDAct: saved pre-activations
   const bf16_t* u;
   const bf16_t* zeros;     // at least 16 zero bytes (source of out-of-range reduction indices)
-  unsigned long long* clock;   // null, or where the first workgroup records the clock it ran at
+  unsigned long long* clock;   // null, or where the middle workgroup records the clock it ran at
 };
-
-
 
 template <int KIND, class T>
 __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::kWavesPerSimd, T::kWavesPerSimd))) void row_grouped_kernel(RowArgs p) {
@@ -757,7 +754,7 @@ struct WgradArgs {
   bf16_t* out0; bf16_t* out1; int m_split;     // out1 rows are (m - m_split)
   float* partial;                              // [max_slots][M][N]
   const bf16_t* zeros;     // at least 16 zero bytes
-  unsigned long long* clock;   // null, or where the first workgroup records the clock it ran at
+  unsigned long long* clock;   // null, or where the middle workgroup records the clock it ran at
 };
 
 template <int WHICH, class T>   // WHICH 0: dW_down, 1: [dW_gate; dW_up] (separate symbols so profiles tell them apart)

@@ -857,6 +857,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
 // with a few hundred rows waste little; the weight side is 256 wide.
 typedef Tile<128, 256, 32, 2, 2, 3> TileRow;           // 72 KiB of LDS: two 4-wave workgroups per CU
 typedef Tile<128, 256, 32, 2, 2, 3> TileWgrad;
+typedef Tile<64, 128, 64, 2, 2, 3> TileRouter;         // skinny products with N = E: 72 KiB of LDS, 128-byte row pieces
 typedef Tile<128, 256, 64, 2, 4, 3> TileWide;           // 144 KiB of LDS: one 8-wave workgroup per CU, 64 x 64 per wave, 128-byte row pieces
 
 // 0 = default.  MOE_GEMM_TILE=1 in the environment selects the 64-wide-slab variant for every product: its
@@ -880,9 +881,15 @@ static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 // 2 * ceil(P / chunk) <= 64 partial slots can ever be needed (an expert is split only if it has more than
 // one chunk, and the chunks of split experts hold more than half their rows each but the last).
 static int wgrad_chunk_rows(int P) { return std::max(1024, static_cast<int>(align_up(static_cast<size_t>(ceil_div(P, 32)), 256))); }
-static int wgrad_max_items(int P, int E) { return E + ceil_div(P, wgrad_chunk_rows(P)); }
-static int wgrad_max_split(int P, int E) { return std::max(1, std::min(E, ceil_div(P, wgrad_chunk_rows(P)))); }
-static int wgrad_max_slots(int P) { return 2 * ceil_div(P, wgrad_chunk_rows(P)); }
+static int wgrad_max_items(int P, int E, int chunk) { return E + ceil_div(P, chunk); }
+static int wgrad_max_split(int P, int E, int chunk) { return std::max(1, std::min(E, ceil_div(P, chunk))); }
+static int wgrad_max_slots(int P, int chunk) { return 2 * ceil_div(P, chunk); }
+static int wgrad_max_items(int P, int E) { return wgrad_max_items(P, E, wgrad_chunk_rows(P)); }
+static int wgrad_max_split(int P, int E) { return wgrad_max_split(P, E, wgrad_chunk_rows(P)); }
+static int wgrad_max_slots(int P) { return wgrad_max_slots(P, wgrad_chunk_rows(P)); }
+// The router's weight gradient has a single "expert" of all T rows and only E x d outputs: shorter chunks
+// (at least 64 of them) so that the launch fills the chip.
+static int router_chunk_rows(int T) { return std::max(256, static_cast<int>(align_up(static_cast<size_t>(ceil_div(T, 64)), 256))); }
 
 struct WsLayout {
   size_t tiles_count, zeros, tiles_expert, tiles_row0, dgu, g, u, items, partial, total;
@@ -1095,18 +1102,19 @@ static RouterWs router_ws(int T, int d, int E, bool bwd) {
   size_t off = 0;
   w.tiles_count = off; off += 256;
   w.zeros = off; off += 256;
-  const size_t t = align_up(static_cast<size_t>(max_row_tiles(T, 1)) * sizeof(int32_t), 256);
+  const size_t t = align_up(static_cast<size_t>(ceil_div(T, 64) + 1) * sizeof(int32_t), 256);   // row tiles of 64 or 128 rows
   w.tiles_expert = off; off += t;
   w.tiles_row0 = off; off += t;
   w.dz = off; w.items = off; w.partial = off;
   if (bwd) {
     off += align_up(static_cast<size_t>(T) * E * 2, 256);
     w.items = off;
-    const size_t it = align_up(static_cast<size_t>(wgrad_max_items(T, 1)) * sizeof(int32_t), 256);
-    const size_t sp = align_up(static_cast<size_t>(wgrad_max_split(T, 1)) * sizeof(int32_t), 256);
+    const int chunk = router_chunk_rows(T);
+    const size_t it = align_up(static_cast<size_t>(wgrad_max_items(T, 1, chunk)) * sizeof(int32_t), 256);
+    const size_t sp = align_up(static_cast<size_t>(wgrad_max_split(T, 1, chunk)) * sizeof(int32_t), 256);
     off += 256 + 4 * it + 3 * sp;
     w.partial = off;
-    off += align_up(static_cast<size_t>(wgrad_max_slots(T)) * E * d * sizeof(float), 256);
+    off += align_up(static_cast<size_t>(wgrad_max_slots(T, chunk)) * E * d * sizeof(float), 256);
   }
   w.total = off + 256;
   return w;
@@ -1117,7 +1125,7 @@ size_t router_bwd_ws_bytes_bf16(int T, int d, int E) { return router_ws(T, d, E,
 static RowTiles router_tiles_at(void* ws, const RouterWs& w, int T) {
   char* b = static_cast<char*>(ws);
   RowTiles rt;
-  rt.max_tiles = max_row_tiles(T, 1);
+  rt.max_tiles = ceil_div(T, 64) + 1;
   rt.count = reinterpret_cast<int32_t*>(b + w.tiles_count);
   rt.zeros = reinterpret_cast<uint32_t*>(b + w.zeros);
   rt.expert = reinterpret_cast<int32_t*>(b + w.tiles_expert);
@@ -1129,13 +1137,13 @@ void router_fwd_bf16(const RouterFwdArgs& a) {
   const RouterWs w = router_ws(a.T, a.d, a.E, false);
   const RowTiles rt = router_tiles_at(a.ws, w, a.T);
   MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, static_cast<const int32_t*>(nullptr), 1, a.T,
-             row_bm(), rt);
+             TileRouter::BM, rt);
   RowArgs p{};
   p.a = static_cast<const bf16_t*>(a.x); p.lda = a.d;
   p.w0 = static_cast<const bf16_t*>(a.w_router); p.w_expert_stride = 0; p.ldw = a.d;
   p.K = a.d; p.N = a.E; p.offsets = nullptr; p.P = a.T; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
   p.out_f32 = a.logits; p.ldo = a.E;
-  launch_row<kRouterFwd>(p, a.T, 1, a.stream);
+  launch_row_t<kRouterFwd, TileRouter>(p, a.T, 1, a.stream);
 }
 
 void router_bwd_bf16(const RouterBwdArgs& a) {
@@ -1159,9 +1167,9 @@ void router_bwd_bf16(const RouterBwdArgs& a) {
     WgradItems items;
     {
       char* b = base + w.items;
-      items.max_items = wgrad_max_items(a.T, 1);
-      items.max_split = wgrad_max_split(a.T, 1);
-      items.max_slots = wgrad_max_slots(a.T);
+      items.max_items = wgrad_max_items(a.T, 1, router_chunk_rows(a.T));
+      items.max_split = wgrad_max_split(a.T, 1, router_chunk_rows(a.T));
+      items.max_slots = wgrad_max_slots(a.T, router_chunk_rows(a.T));
       const size_t li = align_up(static_cast<size_t>(items.max_items) * sizeof(int32_t), 256);
       const size_t ls = align_up(static_cast<size_t>(items.max_split) * sizeof(int32_t), 256);
       items.count = reinterpret_cast<int32_t*>(b); b += 256;
@@ -1174,7 +1182,7 @@ void router_bwd_bf16(const RouterBwdArgs& a) {
       items.split_n = reinterpret_cast<int32_t*>(b);
     }
     MOE_LAUNCH("build_wgrad_items", build_wgrad_items_kernel, dim3(1), dim3(1024), 0, a.stream, static_cast<const int32_t*>(nullptr), 1, a.T,
-               wgrad_chunk_rows(a.T), items);
+               router_chunk_rows(a.T), items);
     WgradArgs p{};
     p.lhs = dz; p.ld_lhs = a.E; p.M = a.E;
     p.rhs = static_cast<const bf16_t*>(a.x); p.ld_rhs = a.d; p.N = a.d;

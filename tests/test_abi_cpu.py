@@ -75,6 +75,17 @@ def test_bad_arguments_are_rejected_before_any_launch(L):
     assert lib.moe_unpermute_combine_bwd(one, one, 1, 4, 64, 2, None, one, one, one, None) == L.MOE_ERR_INVALID_ARG
     # route backward needs logits when renorm == 0
     assert lib.moe_route_topk_bwd(one, one, one, None, 4, 8, 2, 0, one, None) == L.MOE_ERR_INVALID_ARG
+    # router linear: E not a multiple of 8 for bf16, null pointers, workspace, misalignment; fp32 has no such limit
+    assert lib.moe_router_logits(one, one, 1, 16, 64, 12, one, one, 1 << 20, None) == L.MOE_ERR_UNSUPPORTED
+    assert "E=12" in L.moe_last_error()
+    assert lib.moe_router_logits(one, None, 1, 16, 64, 16, one, one, 1 << 20, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_router_logits(one, one, 1, 16, 64, 16, one, one, 8, None) == L.MOE_ERR_WORKSPACE
+    assert lib.moe_router_logits(odd, one, 0, 16, 64, 12, one, one, 1 << 20, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_router_logits(one, one, 1, 0, 64, 16, one, one, 1 << 20, None) == L.MOE_OK      # no tokens
+    assert lib.moe_router_bwd(one, one, one, 1, 16, 64, 2048, 0, one, one, one, 1 << 30, None) == L.MOE_ERR_UNSUPPORTED
+    assert lib.moe_router_bwd(one, one, one, 1, 16, 64, 16, 0, None, one, one, 1 << 30, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_router_bwd(one, one, one, 1, 16, 64, 16, 0, one, one, one, 8, None) == L.MOE_ERR_WORKSPACE
+    assert lib.moe_router_bwd_workspace_bytes(L.MOE_BF16, 8192, 2048, 128) >= 8192 * 128 * 2
     # zero tokens is a no-op, not an error (nothing is launched for the movers)
     assert lib.moe_unpermute_combine_fwd(None, 1, 0, 64, 2, None, None, None, None) == L.MOE_OK
 

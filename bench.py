@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--workload", default="a3b_8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-save-gu", action="store_true", help="backward recomputes G and U")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (removes launch overhead; matters "
+                         "for the small workloads only)")
     ap.add_argument("--router", action="store_true",
                     help="start from hidden states: the router linear and its backward are part of the step "
                          "(the default step starts from given logits, as the metric's path does)")
@@ -144,9 +147,23 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run = step
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        run = graph.replay
+        run()
+        torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / args.steps
@@ -201,7 +218,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "k": cfg.k, "f": cfg.f, "P": P,
-                   "renorm": cfg.renorm, "save_gu": not args.no_save_gu, "router_linear_in_step": bool(args.router),
+                   "renorm": cfg.renorm, "save_gu": not args.no_save_gu, "router_linear_in_step": bool(args.router), "hip_graph": bool(args.graph),
                    "unit_note": "routed rows/s" if prerouted else "tokens/s"},
         "roofline": roofline,
         "grouped_gemm": {"tflops": round(gemm_tflops, 2), "frac_of_peak": round(gemm_tflops / gemm_peak, 4),

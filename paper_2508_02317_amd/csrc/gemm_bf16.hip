@@ -1,7 +1,7 @@
 // bf16 MFMA grouped GEMMs of the SwiGLU expert FFN, forward and backward
 // (Sec. 3.2.5 SwiGLU among the efficient kernels; App. B.6 stacked expert-major weights).
 //
-// One kernel skeleton serves all nine matrix products of the layer:
+// One kernel skeleton serves all nine matrix products of the layer (and the three of the router):
 //   * a BM x BN output tile per 256-thread workgroup: 2 x 2 wavefronts, each owning a
 //     WM x WN sub-tile made of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, fp32
 //     accumulators kept in registers for the whole reduction);
@@ -22,10 +22,13 @@
 //     that each group of lanes the LDS serves in one cycle covers all 64 banks.
 // Row-grouped products (rows of the activation matrix belong to experts) take their
 // (expert, row-tile) list from a small schedule built on the device from `offsets`, so no
-// host synchronisation is needed; weight-gradient products are grouped along the
-// reduction dimension instead and have a host-known grid.
+// host synchronisation is needed.  Weight-gradient products reduce over an expert's rows
+// instead: a second device-built schedule cuts long experts into bounded chunks whose fp32
+// partial tiles a small kernel adds in chunk order (no float atomics).
 // Workgroup ids are remapped so that consecutive tiles -- which share an expert's weights
-// -- run on the same XCD and hit its L2.
+// -- run on the same XCD (workgroup b runs on XCD b mod 8) and hit its L2.
+// The router linear (logits, its weight gradient, its part of the input gradient) runs on
+// the same skeleton with a single segment of all rows.
 #include <algorithm>
 #include <cstdlib>
 #include "moe_common.h"

@@ -122,3 +122,44 @@ def test_full_size_ep_share_skewed():
     order = np.argsort(counts)
     experts = sorted({int(order[-1]), int(order[len(order) // 2]), int(order[0]), int(order[1])})
     _check_sampled(cfg, inp, X, layer, lidx, lw32.astype(np.float64), None, tokens, experts)
+
+
+def test_full_size_block_from_hidden_states():
+    """a3b_8k with the router linear in front: logits against the fp64 product, routing on the GPU's own
+    logits, the whole dW_router, and Y / dX (expert + router path) on sampled tokens."""
+    import torch
+    from paper_2508_02317_amd.layer import MoELayer
+    cfg = CONFIGS["a3b_8k"]
+    say("full size a3b_8k from hidden states: T=%d" % cfg.T)
+    inp = make_inputs(cfg)
+    dt = cfg.dtype
+    Wr = np.ascontiguousarray(inp["Wr"].T)                           # [E, d]
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), to_dev(inp["Wg"], dt), to_dev(inp["Wu"], dt),
+                     to_dev(inp["Wd"], dt), renorm=cfg.renorm, w_router=to_dev(Wr, dt))
+    layer.forward(to_dev(inp["X"], dt))
+    layer.backward(to_dev(inp["dY"], dt))
+    torch.cuda.synchronize()
+    z = to_np(layer.logits)
+    assert rel_err(z, O.router_logits(inp["X"], Wr)) <= 1e-5
+    idx, w, counts, offsets = O.route_topk(z, cfg.k, cfg.renorm)     # the oracle routes on the same fp32 logits
+    assert np.array_equal(to_np(layer.topk_idx), idx) and np.array_equal(to_np(layer.offsets), offsets)
+    r = np.random.default_rng(cfg.seed + 100)
+    tokens = sorted(r.choice(cfg.T, size=10, replace=False).tolist())
+    dz = to_np(layer.dlogits).astype(np.float64)
+    from paper_2508_02317_amd.inputs import quantise
+    dz_seen = quantise(dz.astype(np.float32), dt).astype(np.float64)  # the backward products use dz rounded to bf16
+    got_y, got_dx, ref_y, ref_dx, ref_dz = [], [], [], [], []
+    for t in tokens:
+        ry, rdx, rdw = O.token_fwd_bwd(inp["X"][t], idx[t], w[t], inp["dY"][t], inp["Wg"], inp["Wu"], inp["Wd"])
+        rdz = O.route_topk_bwd(rdw[None], w[t][None], idx[t][None], z[t][None], cfg.E, cfg.renorm)[0]
+        ref_y.append(ry); ref_dz.append(rdz)
+        ref_dx.append(rdx + dz_seen[t] @ Wr.astype(np.float64))
+        got_y.append(to_np(layer.y)[t]); got_dx.append(to_np(layer.dx)[t])
+    tol = TOL[dt]
+    errs = {"Y": rel_err(np.array(got_y), np.array(ref_y)), "dX": rel_err(np.array(got_dx), np.array(ref_dx)),
+            "dlogits": rel_err(dz[tokens], np.array(ref_dz))}
+    _, rdWr = O.router_bwd(dz_seen, inp["X"], Wr)
+    errs["dW_router"] = rel_err(to_np(layer.dw_router), rdWr)
+    say("  errors: " + " ".join("%s=%.2e" % kv for kv in errs.items()))
+    for key, v in errs.items():
+        assert v <= tol, "%s: %.3e > %.1e" % (key, v, tol)

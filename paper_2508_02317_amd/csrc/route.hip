@@ -13,7 +13,7 @@ namespace moe {
 
 constexpr int kRouteThreads = 256;                 // 4 waves
 constexpr int kRouteWaves = kRouteThreads / 64;
-constexpr int kRouteMaxBlocks = 512;
+constexpr int kRouteMaxBlocks = 2048;
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o) {
   uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), o, 64);
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_bwd_kernel(
 }
 
 static int route_blocks(int T) {
-  int b = ceil_div(T, kRouteWaves * 8);   // about 8 tokens per wave
+  int b = ceil_div(T, kRouteWaves * 2);   // about 2 tokens per wave: the per-token chain of wave reductions is latency-bound, so many waves
   return b < 1 ? 1 : (b > kRouteMaxBlocks ? kRouteMaxBlocks : b);
 }
 

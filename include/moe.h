@@ -183,8 +183,9 @@ int32_t moe_router_bwd(const float* dlogits, const void* x, const void* w_router
  * Per-kernel timing for measurement harnesses (not part of the layer's arithmetic).
  * moe_profile_enable(1): from now on every kernel the library launches is bracketed by a
  * pair of HIP events recorded on the launch stream (the library creates the events it
- * needs; this is the only place it allocates anything).  moe_profile_enable(0) stops it.
- * Either call discards records not yet reported.
+ * needs; this is the only place it allocates anything); records made so far are dropped.
+ * moe_profile_enable(0) pauses the recording and keeps the records; moe_profile_enable(2)
+ * resumes it without dropping anything (so a harness can sample some of its steps).
  * moe_profile_report: waits for the recorded events, writes one line per kernel
  * "name launches total_milliseconds\n" into buf ([host], cap bytes, NUL-terminated,
  * truncated if too small), clears the records and returns the size needed.

@@ -87,11 +87,13 @@ extern "C" int32_t moe_profile_enable(int on) {
       return fail(MOE_ERR_HIP, "moe_profile_enable: cannot allocate the clock slots");
     }
   }
-  if (on && hipMemset(g_prof_clock, 0, kClockSlots * 2 * sizeof(unsigned long long)) != hipSuccess)
-    return fail(MOE_ERR_HIP, "moe_profile_enable: cannot clear the clock slots");
-  for (auto& r : g_prof_records) g_prof_pool.emplace_back(r.start, r.stop);
-  g_prof_records.clear();
-  g_prof_on = on != 0;
+  if (on == 1) {                                       // a fresh start: drop what was recorded so far
+    if (hipMemset(g_prof_clock, 0, kClockSlots * 2 * sizeof(unsigned long long)) != hipSuccess)
+      return fail(MOE_ERR_HIP, "moe_profile_enable: cannot clear the clock slots");
+    for (auto& r : g_prof_records) g_prof_pool.emplace_back(r.start, r.stop);
+    g_prof_records.clear();
+  }
+  g_prof_on = on != 0;                                 // 0: pause (records stay), 2: resume
   return MOE_OK;
 }
 

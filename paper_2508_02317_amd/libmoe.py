@@ -103,7 +103,8 @@ def moe_last_error():
 
 
 def moe_profile_enable(on):
-    _check(lib.moe_profile_enable(int(bool(on))))
+    """1: start afresh, 0: pause (records are kept), 2: resume."""
+    _check(lib.moe_profile_enable(int(on)))
 
 
 def moe_profile_shader_clock():

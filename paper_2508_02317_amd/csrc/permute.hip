@@ -68,6 +68,21 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(
 }
 
 // ---- step 3: maps + row gather ------------------------------------------------------------
+
+// The combine kernels stream their rows: every source piece is read once and every destination piece written
+// once, to be consumed by a later kernel.  Non-temporal accesses keep them from displacing what the neighbouring
+// kernels share through the L2 (measured: 5-8 % on combine_fwd, 2 % on the kernels that follow).  The gather of
+// the permutation is faster with ordinary accesses and keeps them.
+typedef unsigned int mover_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_stream(const uint4* p) {
+  const mover_u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const mover_u32x4*>(p));
+  return make_uint4(w.x, w.y, w.z, w.w);
+}
+__device__ __forceinline__ void store16_stream(uint4* p, const uint4& v) {
+  const mover_u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<mover_u32x4*>(p));
+}
+
 // One wave per token; a row is d*elem bytes = n16 sixteen-byte pieces.
 __global__ __launch_bounds__(kMoverThreads) void permute_gather_kernel(
     const uint4* __restrict__ x, int T, int k, int E, int n16, const int32_t* __restrict__ topk_idx,
@@ -159,7 +174,7 @@ __global__ __launch_bounds__(kMoverThreads) void combine_fwd_kernel(
     }
     uint4 v[KB];
 #pragma unroll
-    for (int u = 0; u < KB; ++u) v[u] = yp[static_cast<size_t>(r[u]) * n16 + c];
+    for (int u = 0; u < KB; ++u) v[u] = load16_stream(yp + static_cast<size_t>(r[u]) * n16 + c);
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
       if (j + u < k) {
@@ -170,7 +185,7 @@ __global__ __launch_bounds__(kMoverThreads) void combine_fwd_kernel(
       }
     }
   }
-  y[piece] = Piece<DT>::pack(acc);
+  store16_stream(y + piece, Piece<DT>::pack(acc));
 }
 
 // ---- combine backward: dyp[row] = w * dy[t];  dw[t,j] = <dy[t], yp[row]> --------------------
@@ -203,7 +218,7 @@ __global__ __launch_bounds__(kMoverThreads) void combine_bwd_kernel(
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         int c = c0 + u * 64 + lane;
-        if (c < n16) { a[u] = dyr[c]; b[u] = src[c]; }
+        if (c < n16) { a[u] = dyr[c]; b[u] = load16_stream(src + c); }
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -214,7 +229,7 @@ __global__ __launch_bounds__(kMoverThreads) void combine_bwd_kernel(
           Piece<DT>::unpack(b[u], fb);
 #pragma unroll
           for (int i = 0; i < N; ++i) { dot = fmaf(fa[i], fb[i], dot); fo[i] = wj * fa[i]; }
-          dst[c] = Piece<DT>::pack(fo);
+          store16_stream(dst + c, Piece<DT>::pack(fo));
         }
       }
     }

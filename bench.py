@@ -30,15 +30,15 @@ PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (
 # command summarised under profiles/, each counter scaled by what it reads for a plain 1 GiB copy
 # (fetch x 2.000, write x 1.000).  Keyed by (workload, kernel); absent = not measured.
 MEASURED_TRAFFIC = {
-    ("a3b_8k", "ffn_gate_up"): 2309.9e6 + 302.0e6,
-    ("a3b_8k", "ffn_down"): 811.6e6 + 268.4e6,
-    ("a3b_8k", "ffn_dact"): 967.9e6 + 201.3e6,
-    ("a3b_8k", "ffn_dx"): 1938.1e6 + 268.4e6,
-    ("a3b_8k", "wgrad_down"): 420.7e6 + 402.7e6,
-    ("a3b_8k", "wgrad_gate_up"): 737.3e6 + 805.3e6,
+    ("a3b_8k", "ffn_gate_up"): 2229.1e6 + 302.0e6,
+    ("a3b_8k", "ffn_down"): 721.6e6 + 268.4e6,
+    ("a3b_8k", "ffn_dact"): 963.9e6 + 201.3e6,
+    ("a3b_8k", "ffn_dx"): 1881.2e6 + 268.4e6,
+    ("a3b_8k", "wgrad_down"): 376.8e6 + 402.7e6,
+    ("a3b_8k", "wgrad_gate_up"): 503.1e6 + 805.3e6,
     ("a3b_8k", "permute_gather"): 35.2e6 + 270.1e6,
-    ("a3b_8k", "combine_fwd"): 270.6e6 + 33.6e6,
-    ("a3b_8k", "combine_bwd"): 492.5e6 + 268.7e6,
+    ("a3b_8k", "combine_fwd"): 270.1e6 + 33.6e6,
+    ("a3b_8k", "combine_bwd"): 315.0e6 + 268.7e6,
 }
 
 

@@ -11,9 +11,9 @@
 
 namespace moe {
 
-constexpr int kRouteThreads = 256;                 // 4 waves
+constexpr int kRouteThreads = 1024;                // 16 waves: few histogram rows for the scan, many waves in flight
 constexpr int kRouteWaves = kRouteThreads / 64;
-constexpr int kRouteMaxBlocks = 2048;
+constexpr int kRouteMaxBlocks = 1024;
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o) {
   uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), o, 64);

@@ -105,6 +105,8 @@ int32_t moe_route_topk_bwd(const float* dw, const float* topk_w, const int32_t* 
  *   x [T,d] in; topk_idx [T,k] in; offsets [E+1] in (as written by moe_route_topk, or the
  *   exclusive scan of the bincount of topk_idx for pre-routed rows with k = 1);
  *   xp [P,d] out; row_of_pair, pair_of_row [P] i32 out.
+ * x and xp may both be NULL: only the two maps are written (for the *_gather calls below, which
+ * read x by token and need no xp).
  */
 size_t moe_permute_workspace_bytes(int T, int E, int k);
 int32_t moe_permute(const void* x, int dtype, int T, int d, int E, int k,
@@ -138,6 +140,41 @@ int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, const void*
                                     const void* w_up, const void* w_down, int dtype, int P, int d,
                                     int f, int E, const int32_t* offsets, void* dxp, void* dw_gate,
                                     void* dw_up, void* dw_down, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * The same grouped FFN with the dispatch folded into the products (Sec. 3.2.3 dispatch, Sec. 3.2.5
+ * fused kernels): the rows of an expert are read from the token-major matrices while the tiles are
+ * loaded, so neither xp nor the expert-ordered output gradient dyp is ever written.  P == T*k;
+ * row r stands for pair pair_of_row[r], i.e. token pair_of_row[r] / k with weight topk_w[pair_of_row[r]].
+ * T * d * element size must stay below 4 GiB.
+ *
+ * Forward: exactly moe_grouped_gemm_swiglu_fwd applied to xp[r] = x[pair_of_row[r] / k].
+ *   x [T,d] in; pair_of_row [P] in (from moe_permute); the rest as in moe_grouped_gemm_swiglu_fwd.
+ *
+ * Backward: exactly moe_unpermute_combine_bwd followed by moe_grouped_gemm_swiglu_bwd, i.e. with
+ * dyp[r] = topk_w[pair] * dy[token] never stored:
+ *   dA = topk_w[pair] * (dy[token] W_down[e]);   dW_down[e] = dy[token]^T (topk_w[pair] * act);
+ *   dtopk_w[pair] = <dy[token] W_down[e], act[r]>  ( = <dy[token], yp[r]> );
+ *   dG, dU, dW_gate, dW_up, dxp as in moe_grouped_gemm_swiglu_bwd with xp[r] = x[token].
+ *   dy, x [T,d] in; topk_w [T,k] f32 in; g_save, u_save [P,f] in, or both NULL (recomputed from x);
+ *   dxp [P,d] out (moe_unpermute_combine_fwd with NULL weights turns it into dx); dw_* out;
+ *   dtopk_w [T,k] f32 out (input of moe_route_topk_bwd).  act and yp are not needed.
+ * For bf16, act is recomputed from the rounded G and U in fp32, and topk_w * act is rounded once.
+ */
+size_t moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(int dtype, int P, int d, int f, int E);
+int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int k, const int32_t* pair_of_row,
+                                           const void* w_gate, const void* w_up, const void* w_down,
+                                           int dtype, int P, int d, int f, int E, const int32_t* offsets,
+                                           void* g_save, void* u_save, void* act, void* yp,
+                                           void* ws, size_t ws_bytes, void* stream);
+size_t moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(int dtype, int P, int d, int f, int E, int have_saved);
+int32_t moe_grouped_gemm_swiglu_bwd_gather(const void* dy, const void* x, int T, int k, const float* topk_w,
+                                           const int32_t* pair_of_row, const void* g_save,
+                                           const void* u_save, const void* w_gate, const void* w_up,
+                                           const void* w_down, int dtype, int P, int d, int f, int E,
+                                           const int32_t* offsets, void* dxp, void* dw_gate, void* dw_up,
+                                           void* dw_down, float* dtopk_w, void* ws, size_t ws_bytes,
+                                           void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Weighted un-permute / combine (the return half of the dispatch of Sec. 3.2.3).

@@ -186,6 +186,67 @@ extern "C" int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, 
   return check_launch("moe_grouped_gemm_swiglu_bwd");
 }
 
+// ---- grouped FFN reading its rows by token (no expert-ordered copies) -------------------------------------
+static int32_t check_gather_dims(const char* who, int dtype, int T, int k, int P, int d) {
+  MOE_REQUIRE(T >= 0 && k > 0 && static_cast<int64_t>(T) * k == P, MOE_ERR_INVALID_ARG, "%s: need P == T * k (T=%d k=%d P=%d)", who, T, k, P);
+  // the kernels address a token's row with a 32-bit byte offset
+  MOE_REQUIRE(static_cast<int64_t>(T) * d * elem_size(dtype) < (int64_t{1} << 32) - 65536, MOE_ERR_UNSUPPORTED,
+              "%s: T * d * element size must stay below 4 GiB (T=%d d=%d)", who, T, d);
+  return MOE_OK;
+}
+
+extern "C" size_t moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(int dtype, int P, int d, int f, int E) {
+  if (P < 0 || d <= 0 || f <= 0 || E <= 0) return 0;
+  return dtype == MOE_BF16 ? ffn_fwd_gather_ws_bytes_bf16(P, d, f, E) : ffn_fwd_gather_ws_bytes_f32(P, d, f, E);
+}
+
+extern "C" size_t moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(int dtype, int P, int d, int f, int E, int have_saved) {
+  if (P < 0 || d <= 0 || f <= 0 || E <= 0) return 0;
+  return dtype == MOE_BF16 ? ffn_bwd_gather_ws_bytes_bf16(P, d, f, E, have_saved) : ffn_bwd_gather_ws_bytes_f32(P, d, f, E, have_saved);
+}
+
+extern "C" int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int k, const int32_t* pair_of_row, const void* w_gate,
+                                                      const void* w_up, const void* w_down, int dtype, int P, int d, int f, int E,
+                                                      const int32_t* offsets, void* g_save, void* u_save, void* act, void* yp,
+                                                      void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_ffn_dims("ffn_fwd_gather", dtype, P, d, f, E)) return rc;
+  if (int32_t rc = check_gather_dims("ffn_fwd_gather", dtype, T, k, P, d)) return rc;
+  MOE_REQUIRE((g_save == nullptr) == (u_save == nullptr), MOE_ERR_INVALID_ARG, "ffn_fwd_gather: g_save and u_save must both be given or both be null");
+  if (P == 0) return MOE_OK;
+  MOE_REQUIRE(x && pair_of_row && w_gate && w_up && w_down && offsets && act && yp, MOE_ERR_INVALID_ARG, "ffn_fwd_gather: null pointer");
+  MOE_REQUIRE(aligned16(x) && aligned16(w_gate) && aligned16(w_up) && aligned16(w_down) && aligned16(act) && aligned16(yp) &&
+              aligned16(g_save) && aligned16(u_save), MOE_ERR_INVALID_ARG, "ffn_fwd_gather: tensors must be 16-byte aligned");
+  const size_t need = moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(dtype, P, d, f, E);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_fwd_gather: workspace null, misaligned or smaller than %zu bytes", need);
+  FfnFwdGatherArgs a{x, T, k, pair_of_row, w_gate, w_up, w_down, P, d, f, E, offsets, g_save, u_save, act, yp, ws,
+                     static_cast<hipStream_t>(stream)};
+  if (dtype == MOE_BF16) ffn_fwd_gather_bf16(a); else ffn_fwd_gather_f32(a);
+  return check_launch("moe_grouped_gemm_swiglu_fwd_gather");
+}
+
+extern "C" int32_t moe_grouped_gemm_swiglu_bwd_gather(const void* dy, const void* x, int T, int k, const float* topk_w,
+                                                      const int32_t* pair_of_row, const void* g_save, const void* u_save,
+                                                      const void* w_gate, const void* w_up, const void* w_down, int dtype, int P,
+                                                      int d, int f, int E, const int32_t* offsets, void* dxp, void* dw_gate,
+                                                      void* dw_up, void* dw_down, float* dtopk_w, void* ws, size_t ws_bytes,
+                                                      void* stream) {
+  if (int32_t rc = check_ffn_dims("ffn_bwd_gather", dtype, P, d, f, E)) return rc;
+  if (int32_t rc = check_gather_dims("ffn_bwd_gather", dtype, T, k, P, d)) return rc;
+  MOE_REQUIRE((g_save == nullptr) == (u_save == nullptr), MOE_ERR_INVALID_ARG, "ffn_bwd_gather: g_save and u_save must both be given or both be null");
+  MOE_REQUIRE(offsets && dw_gate && dw_up && dw_down, MOE_ERR_INVALID_ARG, "ffn_bwd_gather: null offsets or weight-gradient pointer");
+  MOE_REQUIRE(P == 0 || (dy && x && topk_w && pair_of_row && w_gate && w_up && w_down && dxp && dtopk_w), MOE_ERR_INVALID_ARG,
+              "ffn_bwd_gather: null pointer");
+  MOE_REQUIRE(aligned16(dy) && aligned16(x) && aligned16(g_save) && aligned16(u_save) && aligned16(w_gate) && aligned16(w_up) &&
+              aligned16(w_down) && aligned16(dxp) && aligned16(dw_gate) && aligned16(dw_up) && aligned16(dw_down),
+              MOE_ERR_INVALID_ARG, "ffn_bwd_gather: tensors must be 16-byte aligned");
+  const size_t need = moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(dtype, P, d, f, E, g_save != nullptr);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_bwd_gather: workspace null, misaligned or smaller than %zu bytes", need);
+  FfnBwdGatherArgs a{dy, x, T, k, topk_w, pair_of_row, g_save, u_save, w_gate, w_up, w_down, P, d, f, E, offsets, dxp, dw_gate,
+                     dw_up, dw_down, dtopk_w, ws, static_cast<hipStream_t>(stream)};
+  if (dtype == MOE_BF16) ffn_bwd_gather_bf16(a); else ffn_bwd_gather_f32(a);
+  return check_launch("moe_grouped_gemm_swiglu_bwd_gather");
+}
+
 // ---- router linear -----------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) {
   const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;

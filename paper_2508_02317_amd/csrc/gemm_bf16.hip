@@ -64,6 +64,11 @@ struct Operand {
   const bf16_t* half[2];
   long ld;
   int valid[2];      // rows of each half that exist (others read as zero); multiples of 8 if k-strided
+  // Gathered operands (the matrix is [*, ld] and never copied into expert order): logical row r of the
+  // operand -- a tile row if k-contiguous, a reduction index if k-strided -- is memory row gather[grow + r]
+  // of half[0]; half[1] is not used, and every byte offset (row * ld * 2) must fit in 32 bits.
+  const int32_t* gather;
+  int grow;
 };
 
 // ---- LDS layouts ---------------------------------------------------------------------------------
@@ -120,14 +125,32 @@ __device__ __forceinline__ bf16x8 read_frag(const char* p) {
 // 32-bit per-lane offset.  Rows that do not exist are redirected to the tile's first row: they only
 // feed output rows / columns that are never stored.  Reduction indices beyond K (last, partial
 // slab only) are redirected to a block of zeros, so they contribute nothing.
-template <bool KS, int ROWS, int BK, int WAVES> struct Dma {
+template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma {
   static constexpr int CHUNKS = ROWS * BK * 2 / 1024;
   static constexpr int N = CHUNKS / WAVES;                   // chunks per wave
   static_assert(N >= 1 && CHUNKS % WAVES == 0, "tile too small for this many waves");
+  static constexpr int KPC = KS ? 1024 / (ROWS * 2) : 1;      // k-strided: reduction rows per chunk
+  static constexpr int NR = N * KPC;                         // k-strided: reduction rows per wave and slab (consecutive)
   const char* base[N];       // wave-uniform
   uint32_t voff[N];          // per lane, bytes
   int kidx[N];               // per lane: reduction index inside the slab of this lane's piece
   long step;                 // bytes per slab (uniform)
+  // gathered k-strided operand: the memory rows of the wave's NR reduction rows of the next slab to be
+  // issued, fetched with scalar loads one slab ahead (they do not touch the vector-memory counter
+  // that orders the ring)
+  typedef __attribute__((address_space(4))) const int32_t* RowList;
+  typedef int32_t RowVec __attribute__((ext_vector_type(KS && GATHER ? NR : 1)));   // a value, not an array: stays in scalar registers
+  RowList rows;              // wave-uniform: gather + grow + wave * NR
+  RowVec next_row;
+  uint32_t ld2;              // bytes per memory row
+  int lq;                    // per lane: which of the KPC rows of a chunk this lane loads
+  __device__ __forceinline__ void fetch_rows(int slab) {
+    if constexpr (KS && GATHER) {
+      RowList r = rows + slab * BK;
+#pragma unroll
+      for (int j = 0; j < NR; ++j) next_row[j] = r[j];
+    }
+  }
   __device__ __forceinline__ void init(const Operand& op, int wave, int lane) {
     const bf16_t* const h0 = op.half[0];                     // scalars, so that the selects below stay selects
     const bf16_t* const h1 = op.half[1];
@@ -143,16 +166,23 @@ template <bool KS, int ROWS, int BK, int WAVES> struct Dma {
         const bool upper = c * RPC >= ROWS / 2;              // uniform
         const int rh = row - (upper ? ROWS / 2 : 0);
         const int valid = upper ? v1 : v0;
-        // the chunk's base stays the upper half only if the chunk holds at least one row that exists
-        // (uniform); single missing rows are redirected through the per-lane offset
-        const bool chunk_any = (c * RPC - (upper ? ROWS / 2 : 0)) < valid;
-        const bool own_base = !upper || chunk_any;
-        base[i] = reinterpret_cast<const char*>((own_base && upper) ? h1 : h0);
-        const bool own_row = own_base && rh < valid;
-        voff[i] = static_cast<uint32_t>((own_row ? static_cast<long>(rh) * op.ld : 0) * 2 + piece * 16);
+        if constexpr (GATHER) {
+          // rows that do not exist read the tile's first row (it exists)
+          const int mrow = op.gather[op.grow + (rh < valid ? row : 0)];
+          base[i] = reinterpret_cast<const char*>(h0);
+          voff[i] = static_cast<uint32_t>(mrow) * static_cast<uint32_t>(op.ld * 2) + piece * 16;
+        } else {
+          // the chunk's base stays the upper half only if the chunk holds at least one row that exists
+          // (uniform); single missing rows are redirected through the per-lane offset
+          const bool chunk_any = (c * RPC - (upper ? ROWS / 2 : 0)) < valid;
+          const bool own_base = !upper || chunk_any;
+          base[i] = reinterpret_cast<const char*>((own_base && upper) ? h1 : h0);
+          const bool own_row = own_base && rh < valid;
+          voff[i] = static_cast<uint32_t>((own_row ? static_cast<long>(rh) * op.ld : 0) * 2 + piece * 16);
+        }
         kidx[i] = piece * 8;
       } else {
-        constexpr int PPK = ROWS / 8, KPC = 1024 / (ROWS * 2);
+        constexpr int PPK = ROWS / 8;
         const int k = c * KPC + lane / PPK;
         const int phys = lane % PPK;
         const int piece = ((((phys >> 2) ^ (k & 3)) << 2) | (phys & 3));
@@ -162,30 +192,50 @@ template <bool KS, int ROWS, int BK, int WAVES> struct Dma {
         const bool ok = ch < (upper ? v1 : v0);
         // k-strided operands are never dual: half[1] is half[0] shifted by ROWS/2 columns
         base[i] = reinterpret_cast<const char*>(h0);
-        voff[i] = static_cast<uint32_t>(((ok ? col : 0) + static_cast<long>(k) * op.ld) * 2);
+        if constexpr (GATHER) voff[i] = static_cast<uint32_t>((ok ? col : 0) * 2);
+        else voff[i] = static_cast<uint32_t>(((ok ? col : 0) + static_cast<long>(k) * op.ld) * 2);
         kidx[i] = k;
       }
     }
-    step = (KS ? static_cast<long>(BK) * op.ld : BK) * 2;
+    step = (KS ? (GATHER ? 0L : static_cast<long>(BK) * op.ld) : BK) * 2;
+    if constexpr (KS && GATHER) {
+      rows = reinterpret_cast<RowList>(reinterpret_cast<uintptr_t>(op.gather + op.grow + wave * NR));
+      ld2 = static_cast<uint32_t>(op.ld * 2);
+      lq = lane / (ROWS / 8);
+      fetch_rows(0);
+    }
   }
-  // enqueue this wave's share of slab `slab` into the operand tile at `tile` (LDS)
-  __device__ __forceinline__ void issue(int slab, char* tile, int wave) const {
+  // byte offset of this lane's piece of chunk i from the wave-uniform base
+  __device__ __forceinline__ uint32_t lane_off(int i) const {
+    if constexpr (KS && GATHER) {
+      int32_t mrow = next_row[i * KPC];
+#pragma unroll
+      for (int q = 1; q < KPC; ++q) mrow = lq == q ? next_row[i * KPC + q] : mrow;
+      return static_cast<uint32_t>(mrow) * ld2 + voff[i];
+    } else {
+      return voff[i];
+    }
+  }
+  // enqueue this wave's share of slab `slab` into the operand tile at `tile` (LDS); slabs are issued in order
+  __device__ __forceinline__ void issue(int slab, char* tile, int wave) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const char* g = base[i] + slab * step + voff[i];
+      const char* g = base[i] + slab * step + lane_off(i);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                        (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
     }
+    fetch_rows(slab + 1);
   }
   // the same for the last, partial slab: pieces whose reduction index is >= K read zeros
-  __device__ __forceinline__ void issue_tail(int slab, int K, const char* zeros, char* tile, int wave) const {
+  __device__ __forceinline__ void issue_tail(int slab, int K, const char* zeros, char* tile, int wave) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const bool in_range = slab * BK + kidx[i] < K;
-      const char* g = in_range ? base[i] + slab * step + voff[i] : zeros;
+      const char* g = in_range ? base[i] + slab * step + lane_off(i) : zeros;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                        (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
     }
+    fetch_rows(slab + 1);
   }
 };
 
@@ -253,10 +303,10 @@ __device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::N
 // competes with the MFMAs for issue slots.  What limits the stream is the number of L2 requests a
 // CU can have outstanding (about 128, whatever the ring depth): 64-byte row pieces (BK = 32) give
 // about 30 bytes per clock and CU on L2 hits, 128-byte pieces (BK = 64) about 60.
-template <class T, bool A_KS, bool B_KS>
+template <class T, bool A_KS, bool B_KS, bool A_GATHER = false, bool B_GATHER = false>
 struct MainLoop {
-  typedef Dma<A_KS, T::BM, T::BK, T::kWaves> DmaA;
-  typedef Dma<B_KS, T::BN, T::BK, T::kWaves> DmaB;
+  typedef Dma<A_KS, T::BM, T::BK, T::kWaves, A_GATHER> DmaA;
+  typedef Dma<B_KS, T::BN, T::BK, T::kWaves, B_GATHER> DmaB;
   static constexpr int L = DmaA::N + DmaB::N;          // loads per thread per slab
   static constexpr int S = T::kStages;
   static constexpr int STEPS = T::BK / 16;             // reduction steps per slab (even)
@@ -364,11 +414,15 @@ struct MainLoop {
       oa.ld = opA[0].ld;
       oa.valid[0] = opA[0].valid[0];
       oa.valid[1] = opA[0].valid[1];
+      oa.gather = opA[0].gather;
+      oa.grow = opA[0].grow;
       ob.half[0] = seg ? opB[1].half[0] : opB[0].half[0];
       ob.half[1] = seg ? opB[1].half[1] : opB[0].half[1];
       ob.ld = opB[0].ld;
       ob.valid[0] = opB[0].valid[0];
       ob.valid[1] = opB[0].valid[1];
+      ob.gather = opB[0].gather;
+      ob.grow = opB[0].grow;
       da.init(oa, wave, lane);
       db.init(ob, wave, lane);
 #pragma unroll
@@ -512,10 +566,22 @@ struct RowArgs {
   const bf16_t* u;
   const bf16_t* zeros;     // at least 16 zero bytes (source of out-of-range reduction indices)
   unsigned long long* clock;   // null, or where the middle workgroup records the clock it ran at
+  // FUSED kernels: `a` is the token-major matrix [T, lda] and row r of the product reads a[row_token[r]]
+  const int32_t* row_token;    // [P (+ padding)]
+  const float* row_w;          // kDAct: combine weight of each row; the product's rows are scaled by it
+  bf16_t* act_w;               // kDAct: [P, N] out, row_w * silu(G) * U
+  float* dw_partial;           // kDAct: [n_tiles_n * WGN][P] out, partial sums of <silu(G) * U, unscaled dA> per row
 };
 
-template <int KIND, class T>
+// FUSED (kGateUp and kDAct only): the activation rows are gathered from the token-major matrix while the
+// tiles are loaded, so no expert-ordered copy of it exists.  For kDAct that matrix is the gradient of the
+// layer output, and the rest of the combine backward rides in the epilogue:
+//   dA = w_r * (dy[token(r)] Wd)              the combine weight scales the product's rows
+//   d w_r = <dy[token(r)], yp[r]> = <dy[token(r)] Wd, act[r]>    reduced over the columns of the tile
+//   act_w[r] = w_r * act[r]                   the operand with which dWd = dy[token]^T act_w needs no dyp
+template <int KIND, class T, bool FUSED = false>
 __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::kWavesPerSimd, T::kWavesPerSimd))) void row_grouped_kernel(RowArgs p) {
+  static_assert(!FUSED || KIND == kGateUp || KIND == kDAct, "only the two products that read activations by token are fused");
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int BM = T::BM, BN = T::BN, WM = T::WM, WN = T::WN, MI = T::MI, NI = T::NI;
   const int n_row_tiles = p.rt.count[0];
@@ -545,9 +611,13 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   opA.ld = p.lda;
   opA.valid[0] = min(rows, BM / 2);
   opA.valid[1] = max(rows - BM / 2, 0);
-  opA.half[0] = p.a + static_cast<long>(row0) * p.lda;
-  opA.half[1] = opA.half[0] + (BM / 2) * p.lda;
+  opA.half[0] = FUSED ? p.a : p.a + static_cast<long>(row0) * p.lda;
+  opA.half[1] = FUSED ? p.a : opA.half[0] + (BM / 2) * p.lda;
+  opA.gather = FUSED ? p.row_token : nullptr;
+  opA.grow = row0;
   opB.ld = p.ldw;
+  opB.gather = nullptr;
+  opB.grow = 0;
 
   if constexpr (KIND == kGateUp) {
     // tile columns: BN/2 gate columns n0.. and the matching BN/2 up columns; each wave gets the
@@ -561,8 +631,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.half[1] = p.w1 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.valid[0] = opB.valid[1] = ncols;
-    { MainLoop<T, false, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc);
-    }
+    { MainLoop<T, false, false, FUSED, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
     constexpr int LPR = HW / 8;                        // lanes per output row (8 columns each)
@@ -609,7 +678,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       // dA = dyp * Wd[e] (dx = dz * Wr): weight is [K, N], reduction strided
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
       opB.half[1] = opB.half[0] + BN / 2;
-      { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
+      { MainLoop<T, false, true, FUSED, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     } else {
       // dxp = dG * Wg[e] + dU * Wu[e] : two reduction segments over the columns of [dG | dU]
       opB.half[0] = p.w0 + e * p.w_expert_stride + n0;
@@ -627,6 +696,47 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     constexpr int LPR = WN / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
     const int cl = wn * WN + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
+    if constexpr (KIND == kDAct && FUSED) {
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        if (mi >= mi_n) break;
+        park_strip<T>(acc[mi], strip, lane);
+#pragma unroll
+        for (int pass = 0; pass < 32 / RPP; ++pass) {
+          const int rs = pass * RPP + lane / LPR;
+          const int r = wm * WM + mi * 32 + rs;
+          const bool live = cl < ncols && r < rows;
+          float part = 0.0f;
+          if (live) {
+            float v[8], g[8], u[8], dg[8], du[8], aw[8];
+            read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, v);
+            const long gi = static_cast<long>(row0 + r) * p.N + n0 + cl;
+            unpack8(*reinterpret_cast<const uint4*>(p.g + gi), g);
+            unpack8(*reinterpret_cast<const uint4*>(p.u + gi), u);
+            const float wr = p.row_w[row0 + r];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              const float sg = sigmoid_fast(g[q]);
+              const float act = g[q] * sg * u[q];
+              part = fmaf(act, v[q], part);
+              const float da = wr * v[q];
+              dg[q] = da * u[q] * (sg * (1.0f + g[q] * (1.0f - sg)));
+              du[q] = da * (g[q] * sg);
+              aw[q] = wr * act;
+            }
+            const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+            store16(p.out0 + o, pack8(dg));
+            store16(p.out0 + o + p.N, pack8(du));
+            store16(p.act_w + gi, pack8(aw));
+          }
+          // the LPR lanes of a row add up their columns; every (column slot, row) is written exactly once
+#pragma unroll
+          for (int o = LPR / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+          if (r < rows && lane % LPR == 0) p.dw_partial[static_cast<long>(nt * T::WGN + wn) * p.P + row0 + r] = part;
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       if (mi >= mi_n) break;
@@ -771,10 +881,16 @@ struct WgradArgs {
   float* partial;                              // [max_slots][M][N]
   const bf16_t* zeros;     // at least 16 zero bytes
   unsigned long long* clock;   // null, or where the middle workgroup records the clock it ran at
+  const int32_t* row_token;    // GATHER kernels: [P + padding], token of each expert-ordered row
 };
 
-template <int WHICH, class T>   // WHICH 0: dW_down, 1: [dW_gate; dW_up] (separate symbols so profiles tell them apart)
+// WHICH 0: dW_down, 1: [dW_gate; dW_up], 2: router (separate symbols so profiles tell them apart).
+// GATHER: the operand that holds one row per token -- lhs for WHICH 0 (the output gradient), rhs for WHICH 1
+// (the layer input) -- is the token-major matrix itself, and reduction row r reads its row row_token[r].
+template <int WHICH, class T, bool GATHER = false>
 __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::kWavesPerSimd, T::kWavesPerSimd))) void wgrad_kernel(WgradArgs p) {
+  static_assert(!GATHER || WHICH < 2, "the router's operands are token-major already");
+  constexpr bool GA = GATHER && WHICH == 0, GB = GATHER && WHICH == 1;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int BM = T::BM, BN = T::BN, WM = T::WM, WN = T::WN, MI = T::MI, NI = T::NI;
   const int per_e = p.tiles_m * p.tiles_n;
@@ -801,16 +917,20 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   for (int i = 0; i < NI; ++i) b_row[i] = wn * WN + i * 32;
   Operand opA, opB;
   opA.ld = p.ld_lhs;
-  opA.half[0] = p.lhs + static_cast<long>(begin) * p.ld_lhs + m0;
+  opA.half[0] = p.lhs + (GA ? 0L : static_cast<long>(begin) * p.ld_lhs) + m0;
   opA.half[1] = opA.half[0] + BM / 2;
   opA.valid[0] = min(mrows, BM / 2);
   opA.valid[1] = max(mrows - BM / 2, 0);
+  opA.gather = GA ? p.row_token : nullptr;
+  opA.grow = begin;
   opB.ld = p.ld_rhs;
-  opB.half[0] = p.rhs + static_cast<long>(begin) * p.ld_rhs + n0;
+  opB.half[0] = p.rhs + (GB ? 0L : static_cast<long>(begin) * p.ld_rhs) + n0;
   opB.half[1] = opB.half[0] + BN / 2;
   opB.valid[0] = min(ncols, BN / 2);
   opB.valid[1] = max(ncols - BN / 2, 0);
-  { MainLoop<T, true, true> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, acc); }
+  opB.gather = GB ? p.row_token : nullptr;
+  opB.grow = begin;
+  { MainLoop<T, true, true, GA, GB> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, acc); }
 
   float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
   constexpr int LPR = WN / 8;
@@ -971,19 +1091,19 @@ static WgradItems wgrad_items_at(void* ws, const WsLayout& w, int P, int E) {
 
 static unsigned padded_grid(int tiles) { return static_cast<unsigned>(ceil_div(tiles < 1 ? 1 : tiles, kXcds) * kXcds); }
 
-template <int KIND, class T>
+template <int KIND, class T, bool FUSED = false>
 static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
   static const char* const names[6] = {"ffn_gate_up", "ffn_down", "ffn_dact", "ffn_dx", "router_logits", "router_dx"};
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&row_grouped_kernel<KIND, T>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&row_grouped_kernel<KIND, T, FUSED>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
     attr_set = true;
   }
   p.n_tiles_n = ceil_div(p.N, KIND == kGateUp ? T::BN / 2 : T::BN);
   p.clock = KIND < 4 ? prof_clock_slot(KIND) : nullptr;
   const unsigned grid = padded_grid((ceil_div(P, T::BM) + E) * p.n_tiles_n);
-  MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);
+  MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T, FUSED>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);
 }
 
 template <int KIND>
@@ -992,11 +1112,11 @@ static void launch_row(const RowArgs& p, int P, int E, hipStream_t s) {
   else launch_row_t<KIND, TileRow>(p, P, E, s);
 }
 
-template <int WHICH, class T>
+template <int WHICH, class T, bool GATHER = false>
 static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<WHICH, T>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<WHICH, T, GATHER>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
     attr_set = true;
   }
@@ -1004,7 +1124,7 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
   const unsigned grid = padded_grid(p.tiles_m * p.tiles_n * p.items.max_items);
-  MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T>), dim3(grid),
+  MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T, GATHER>), dim3(grid),
              dim3(T::kThreads), T::kLdsBytes, s, p);
   const long rblocks = (static_cast<long>(p.M) * p.N + 2047) / 2048;
   const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 256L)), static_cast<unsigned>(p.items.max_split));
@@ -1018,15 +1138,40 @@ static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
   else launch_wgrad_t<WHICH, TileWgrad>(p, s);
 }
 
+// row_token == null: xp is in expert order; else xp is the token-major input and rows are gathered from it
 static void launch_gate_up(const void* xp, const void* wg, const void* wu, int P, int d, int f, int E,
-                           const int32_t* offsets, const RowTiles& rt, void* G, void* U, void* act, hipStream_t s) {
+                           const int32_t* offsets, const RowTiles& rt, void* G, void* U, void* act, hipStream_t s,
+                           const int32_t* row_token = nullptr) {
   RowArgs p{};
+  p.row_token = row_token;
   p.a = static_cast<const bf16_t*>(xp); p.lda = d;
   p.w0 = static_cast<const bf16_t*>(wg); p.w1 = static_cast<const bf16_t*>(wu);
   p.w_expert_stride = static_cast<long>(f) * d; p.ldw = d;
   p.K = d; p.N = f; p.offsets = offsets; p.P = P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
   p.out0 = static_cast<bf16_t*>(G); p.out1 = static_cast<bf16_t*>(U); p.out2 = static_cast<bf16_t*>(act); p.ldo = f;
-  launch_row<kGateUp>(p, P, E, s);
+  if (row_token) launch_row_t<kGateUp, TileRow, true>(p, P, E, s);
+  else launch_row<kGateUp>(p, P, E, s);
+}
+
+static void launch_down(const void* act, const void* wd, int P, int d, int f, int E, const int32_t* offsets,
+                        const RowTiles& rt, void* yp, hipStream_t s) {
+  RowArgs p{};
+  p.a = static_cast<const bf16_t*>(act); p.lda = f;
+  p.w0 = static_cast<const bf16_t*>(wd); p.w_expert_stride = static_cast<long>(d) * f; p.ldw = f;
+  p.K = f; p.N = d; p.offsets = offsets; p.P = P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+  p.out0 = static_cast<bf16_t*>(yp); p.ldo = d;
+  launch_row<kDown>(p, P, E, s);
+}
+
+static void launch_dx(const bf16_t* dgu, const void* wg, const void* wu, int P, int d, int f, int E, const int32_t* offsets,
+                      const RowTiles& rt, void* dxp, hipStream_t s) {
+  RowArgs p{};
+  p.a = dgu; p.lda = 2L * f;
+  p.w0 = static_cast<const bf16_t*>(wg); p.w1 = static_cast<const bf16_t*>(wu);
+  p.w_expert_stride = static_cast<long>(f) * d; p.ldw = d;
+  p.K = f; p.N = d; p.offsets = offsets; p.P = P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+  p.out0 = static_cast<bf16_t*>(dxp); p.ldo = d;
+  launch_row<kDX>(p, P, E, s);
 }
 
 void ffn_fwd_bf16(const FfnFwdArgs& a) {
@@ -1034,12 +1179,7 @@ void ffn_fwd_bf16(const FfnFwdArgs& a) {
   const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
   MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, row_bm(), rt);
   launch_gate_up(a.xp, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.g_save, a.u_save, a.act, a.stream);
-  RowArgs p{};
-  p.a = static_cast<const bf16_t*>(a.act); p.lda = a.f;
-  p.w0 = static_cast<const bf16_t*>(a.w_down); p.w_expert_stride = static_cast<long>(a.d) * a.f; p.ldw = a.f;
-  p.K = a.f; p.N = a.d; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
-  p.out0 = static_cast<bf16_t*>(a.yp); p.ldo = a.d;
-  launch_row<kDown>(p, a.P, a.E, a.stream);
+  launch_down(a.act, a.w_down, a.P, a.d, a.f, a.E, a.offsets, rt, a.yp, a.stream);
 }
 
 void ffn_bwd_bf16(const FfnBwdArgs& a) {
@@ -1065,15 +1205,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     p.out0 = dgu; p.ldo = 2L * a.f; p.g = G; p.u = U;
     launch_row<kDAct>(p, a.P, a.E, a.stream);
   }
-  {  // dxp = dG Wg + dU Wu
-    RowArgs p{};
-    p.a = dgu; p.lda = 2L * a.f;
-    p.w0 = static_cast<const bf16_t*>(a.w_gate); p.w1 = static_cast<const bf16_t*>(a.w_up);
-    p.w_expert_stride = static_cast<long>(a.f) * a.d; p.ldw = a.d;
-    p.K = a.f; p.N = a.d; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
-    p.out0 = static_cast<bf16_t*>(a.dxp); p.ldo = a.d;
-    launch_row<kDX>(p, a.P, a.E, a.stream);
-  }
+  launch_dx(dgu, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.dxp, a.stream);   // dxp = dG Wg + dU Wu
   const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
   float* partial = reinterpret_cast<float*>(base + w.partial);
   MOE_LAUNCH("build_wgrad_items", build_wgrad_items_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P,
@@ -1093,6 +1225,133 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_gate); p.out1 = static_cast<bf16_t*>(a.dw_up); p.m_split = a.f;
     launch_wgrad<1>(p, a.stream);
+  }
+}
+
+// ============================================================================================
+// The same two passes without the expert-ordered copies of the layer input and of the output gradient
+// (the dispatch / return of Sec. 3.2.3 folded into the products that consume the rows):
+//   forward   G, U, act, yp as above, rows read as x[token(r)]                              (no xp)
+//   backward  dA = w_r dy[token(r)] Wd,  dWd = dy[token]^T (w act),  d w = <dy[token] Wd, act>,
+//             [dWg; dWu] = [dG | dU]^T x[token]                                             (no dyp, no yp)
+// token(r) = pair_of_row[r] / k and w_r = topk_w[pair_of_row[r]] are expanded once per call into two
+// row-indexed lists; the list of tokens is padded so that the scalar loads that run one slab ahead of the
+// weight-gradient products never leave it.
+// ============================================================================================
+constexpr int kRowTokenPad = 256;
+
+__global__ __launch_bounds__(256) void build_row_token_kernel(const int32_t* __restrict__ pair_of_row, const float* __restrict__ topk_w,
+                                                               int P, int T, int k, int32_t* __restrict__ row_token,
+                                                               float* __restrict__ row_w) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= P + kRowTokenPad) return;
+  if (r >= P) { row_token[r] = 0; return; }
+  const int pair = min(max(pair_of_row[r], 0), P - 1);
+  row_token[r] = min(pair / k, T - 1);
+  if (row_w) row_w[r] = topk_w[pair];
+}
+
+// dw[pair_of_row[r]] = sum over the column slots, in slot order, of the partial dot products of row r
+__global__ __launch_bounds__(256) void finish_dw_kernel(const float* __restrict__ partial, int slots, int P,
+                                                         const int32_t* __restrict__ pair_of_row, float* __restrict__ dw) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= P) return;
+  float s = 0.0f;
+  for (int j = 0; j < slots; ++j) s += partial[static_cast<long>(j) * P + r];
+  dw[min(max(pair_of_row[r], 0), P - 1)] = s;
+}
+
+static int dw_slots(int f) { return ceil_div(f, TileRow::BN) * TileRow::WGN; }
+
+struct GatherWs { size_t row_token, row_w, act_w, dw_partial, total; };
+static GatherWs gather_ws(const WsLayout& w, int P, int f, bool bwd) {
+  GatherWs g{};
+  size_t off = w.total;
+  g.row_token = off; off += align_up(static_cast<size_t>(P + kRowTokenPad) * sizeof(int32_t), 256);
+  g.row_w = off; g.act_w = off; g.dw_partial = off;
+  if (bwd) {
+    off += align_up(static_cast<size_t>(P) * sizeof(float), 256);
+    g.act_w = off; off += align_up(static_cast<size_t>(P) * f * 2, 256);
+    g.dw_partial = off; off += align_up(static_cast<size_t>(dw_slots(f)) * P * sizeof(float), 256);
+  }
+  g.total = off;
+  return g;
+}
+size_t ffn_fwd_gather_ws_bytes_bf16(int P, int d, int f, int E) {
+  return gather_ws(ws_layout(P, d, f, E, false, false), P, f, false).total;
+}
+size_t ffn_bwd_gather_ws_bytes_bf16(int P, int d, int f, int E, int have_saved) {
+  return gather_ws(ws_layout(P, d, f, E, true, !have_saved), P, f, true).total;
+}
+
+void ffn_fwd_gather_bf16(const FfnFwdGatherArgs& a) {
+  const WsLayout w = ws_layout(a.P, a.d, a.f, a.E, false, false);
+  const GatherWs g = gather_ws(w, a.P, a.f, false);
+  const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
+  int32_t* row_token = reinterpret_cast<int32_t*>(static_cast<char*>(a.ws) + g.row_token);
+  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, TileRow::BM, rt);
+  MOE_LAUNCH("build_row_token", build_row_token_kernel, dim3(ceil_div(a.P + kRowTokenPad, 256)), dim3(256), 0, a.stream,
+             a.pair_of_row, static_cast<const float*>(nullptr), a.P, a.T, a.k, row_token, static_cast<float*>(nullptr));
+  launch_gate_up(a.x, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.g_save, a.u_save, a.act, a.stream, row_token);
+  launch_down(a.act, a.w_down, a.P, a.d, a.f, a.E, a.offsets, rt, a.yp, a.stream);
+}
+
+void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
+  const bool recompute = a.g_save == nullptr;
+  const WsLayout w = ws_layout(a.P, a.d, a.f, a.E, true, recompute);
+  const GatherWs gw = gather_ws(w, a.P, a.f, true);
+  const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
+  char* base = static_cast<char*>(a.ws);
+  bf16_t* dgu = reinterpret_cast<bf16_t*>(base + w.dgu);       // [P, 2f] = [dG | dU]
+  int32_t* row_token = reinterpret_cast<int32_t*>(base + gw.row_token);
+  float* row_w = reinterpret_cast<float*>(base + gw.row_w);
+  bf16_t* act_w = reinterpret_cast<bf16_t*>(base + gw.act_w);
+  float* dw_partial = reinterpret_cast<float*>(base + gw.dw_partial);
+  const bf16_t* G = static_cast<const bf16_t*>(a.g_save);
+  const bf16_t* U = static_cast<const bf16_t*>(a.u_save);
+  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, TileRow::BM, rt);
+  MOE_LAUNCH("build_row_token", build_row_token_kernel, dim3(ceil_div(a.P + kRowTokenPad, 256)), dim3(256), 0, a.stream,
+             a.pair_of_row, a.topk_w, a.P, a.T, a.k, row_token, row_w);
+  if (recompute) {
+    bf16_t* Gr = reinterpret_cast<bf16_t*>(base + w.g);
+    bf16_t* Ur = reinterpret_cast<bf16_t*>(base + w.u);
+    launch_gate_up(a.x, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, Gr, Ur, nullptr, a.stream, row_token);
+    G = Gr; U = Ur;
+  }
+  {  // dA = w (dy[token] Wd) with the SwiGLU derivative, the weight gradient's dot products and w * act
+    RowArgs p{};
+    p.a = static_cast<const bf16_t*>(a.dy); p.lda = a.d;
+    p.w0 = static_cast<const bf16_t*>(a.w_down); p.w_expert_stride = static_cast<long>(a.d) * a.f; p.ldw = a.f;
+    p.K = a.d; p.N = a.f; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+    p.out0 = dgu; p.ldo = 2L * a.f; p.g = G; p.u = U;
+    p.row_token = row_token; p.row_w = row_w; p.act_w = act_w; p.dw_partial = dw_partial;
+    launch_row_t<kDAct, TileRow, true>(p, a.P, a.E, a.stream);
+  }
+  if (a.P > 0)
+    MOE_LAUNCH("finish_dw", finish_dw_kernel, dim3(ceil_div(a.P, 256)), dim3(256), 0, a.stream, dw_partial, dw_slots(a.f), a.P,
+               a.pair_of_row, a.dtopk_w);
+  launch_dx(dgu, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.dxp, a.stream);
+  const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
+  float* partial = reinterpret_cast<float*>(base + w.partial);
+  MOE_LAUNCH("build_wgrad_items", build_wgrad_items_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P,
+             wgrad_chunk_rows(a.P), items);
+  {  // dWd[e] = dy[token]^T (w act)
+    WgradArgs p{};
+    p.lhs = static_cast<const bf16_t*>(a.dy); p.ld_lhs = a.d; p.M = a.d;
+    p.rhs = act_w; p.ld_rhs = a.f; p.N = a.f;
+    p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+    p.out0 = static_cast<bf16_t*>(a.dw_down); p.out1 = p.out0; p.m_split = a.d;
+    p.row_token = row_token;
+    launch_wgrad_t<0, TileWgrad, true>(p, a.stream);
+  }
+  {  // [dWg[e]; dWu[e]] = [dG | dU]^T x[token]
+    WgradArgs p{};
+    p.lhs = dgu; p.ld_lhs = 2L * a.f; p.M = 2 * a.f;
+    p.rhs = static_cast<const bf16_t*>(a.x); p.ld_rhs = a.d; p.N = a.d;
+    p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
+    p.out0 = static_cast<bf16_t*>(a.dw_gate); p.out1 = static_cast<bf16_t*>(a.dw_up); p.m_split = a.f;
+    p.row_token = row_token;
+    launch_wgrad_t<1, TileWgrad, true>(p, a.stream);
   }
 }
 

@@ -21,15 +21,17 @@ __device__ __forceinline__ int expert_of_row(const int32_t* __restrict__ offsets
 }
 
 // G = xp Wg^T, U = xp Wu^T, act = silu(G) * U          one thread per (row, n)
+// Every kernel here that reads one row per routed pair takes an optional list of source rows: with it the
+// operand is the token-major matrix and row r reads its row row_src[r] (no expert-ordered copy exists).
 __global__ __launch_bounds__(kF32Threads) void f32_gate_up_kernel(
     const float* __restrict__ xp, const float* __restrict__ wg, const float* __restrict__ wu,
     int P, int d, int f, int E, const int32_t* __restrict__ offsets,
-    float* __restrict__ G, float* __restrict__ U, float* __restrict__ act) {
+    float* __restrict__ G, float* __restrict__ U, float* __restrict__ act, const int32_t* __restrict__ row_src) {
   const size_t i = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
   if (i >= static_cast<size_t>(P) * f) return;
   const int r = static_cast<int>(i / f), n = static_cast<int>(i % f);
   const int e = expert_of_row(offsets, E, r);
-  const float* x = xp + static_cast<size_t>(r) * d;
+  const float* x = xp + static_cast<size_t>(row_src ? row_src[r] : r) * d;   // row_src: xp is token-major
   const float* g_row = wg + (static_cast<size_t>(e) * f + n) * d;
   const float* u_row = wu + (static_cast<size_t>(e) * f + n) * d;
   float g = 0.0f, u = 0.0f;
@@ -58,19 +60,50 @@ __global__ __launch_bounds__(kF32Threads) void f32_down_kernel(
 __global__ __launch_bounds__(kF32Threads) void f32_dact_kernel(
     const float* __restrict__ dyp, const float* __restrict__ wd, const float* __restrict__ G,
     const float* __restrict__ U, int P, int d, int f, int E, const int32_t* __restrict__ offsets,
-    float* __restrict__ dG, float* __restrict__ dU) {
+    float* __restrict__ dG, float* __restrict__ dU, const int32_t* __restrict__ row_src,
+    const float* __restrict__ row_w, float* __restrict__ dA_unscaled, float* __restrict__ act_w) {
   const size_t i = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
   if (i >= static_cast<size_t>(P) * f) return;
   const int r = static_cast<int>(i / f), n = static_cast<int>(i % f);
   const int e = expert_of_row(offsets, E, r);
-  const float* dy = dyp + static_cast<size_t>(r) * d;
+  const float* dy = dyp + static_cast<size_t>(row_src ? row_src[r] : r) * d;
   const float* w = wd + static_cast<size_t>(e) * d * f + n;
   float da = 0.0f;
   for (int c = 0; c < d; ++c) da = fmaf(dy[c], w[static_cast<size_t>(c) * f], da);
   const float g = G[i], u = U[i];
   const float s = sigmoid_acc(g);
+  if (row_w) {   // the rows of dyp are w_r * dy[token]: scale the product instead, and keep what the combine backward needs
+    dA_unscaled[i] = da;
+    act_w[i] = row_w[r] * (g * s * u);
+    da *= row_w[r];
+  }
   dG[i] = da * u * (s * (1.0f + g * (1.0f - s)));
   dU[i] = da * (g * s);
+}
+
+// gradient of the combine weights: dw[pair_of_row[r]] = <dy[token(r)] Wd, act[r]> = <dy[token(r)], yp[r]>
+__global__ __launch_bounds__(kF32Threads) void f32_dw_kernel(
+    const float* __restrict__ dA_unscaled, const float* __restrict__ G, const float* __restrict__ U, int P, int f,
+    const int32_t* __restrict__ pair_of_row, float* __restrict__ dw) {
+  const int r = blockIdx.x * kF32Threads + threadIdx.x;
+  if (r >= P) return;
+  float s = 0.0f;
+  for (int n = 0; n < f; ++n) {
+    const size_t i = static_cast<size_t>(r) * f + n;
+    const float g = G[i];
+    s = fmaf(g * sigmoid_acc(g) * U[i], dA_unscaled[i], s);
+  }
+  dw[min(max(pair_of_row[r], 0), P - 1)] = s;
+}
+
+__global__ __launch_bounds__(kF32Threads) void f32_row_token_kernel(const int32_t* __restrict__ pair_of_row, const float* __restrict__ topk_w,
+                                                                    int P, int T, int k, int32_t* __restrict__ row_token,
+                                                                    float* __restrict__ row_w) {
+  const int r = blockIdx.x * kF32Threads + threadIdx.x;
+  if (r >= P) return;
+  const int pair = min(max(pair_of_row[r], 0), P - 1);
+  row_token[r] = min(pair / k, T - 1);
+  if (row_w) row_w[r] = topk_w[pair];
 }
 
 // dxp = dG Wg + dU Wu                                    one thread per (row, c)
@@ -95,7 +128,8 @@ __global__ __launch_bounds__(kF32Threads) void f32_dx_kernel(
 // out[e][i][j] = sum over the expert's rows of lhs[r,i] * rhs[r,j]      one thread per (e,i,j)
 __global__ __launch_bounds__(kF32Threads) void f32_wgrad_kernel(
     const float* __restrict__ lhs, int li, const float* __restrict__ rhs, int lj, int E, int P,
-    const int32_t* __restrict__ offsets, float* __restrict__ out) {
+    const int32_t* __restrict__ offsets, float* __restrict__ out, const int32_t* __restrict__ lhs_src,
+    const int32_t* __restrict__ rhs_src) {
   const size_t idx = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
   const size_t per = static_cast<size_t>(li) * lj;
   if (idx >= per * E) return;
@@ -104,7 +138,7 @@ __global__ __launch_bounds__(kF32Threads) void f32_wgrad_kernel(
   float s = 0.0f;
   const int begin = min(max(offsets[e], 0), P), end = min(offsets[e + 1], P);
   for (int r = begin; r < end; ++r)
-    s = fmaf(lhs[static_cast<size_t>(r) * li + i], rhs[static_cast<size_t>(r) * lj + j], s);
+    s = fmaf(lhs[static_cast<size_t>(lhs_src ? lhs_src[r] : r) * li + i], rhs[static_cast<size_t>(rhs_src ? rhs_src[r] : r) * lj + j], s);
   out[idx] = s;
 }
 
@@ -124,7 +158,8 @@ void ffn_fwd_f32(const FfnFwdArgs& a) {
   MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
                      static_cast<const float*>(a.xp), static_cast<const float*>(a.w_gate),
                      static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets,
-                     static_cast<float*>(a.g_save), static_cast<float*>(a.u_save), static_cast<float*>(a.act));
+                     static_cast<float*>(a.g_save), static_cast<float*>(a.u_save), static_cast<float*>(a.act),
+                     static_cast<const int32_t*>(nullptr));
   if (a.yp)
     MOE_LAUNCH("f32_down", f32_down_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream,
                        static_cast<const float*>(a.act), static_cast<const float*>(a.w_down), a.P, a.d, a.f, a.E,
@@ -146,12 +181,13 @@ void ffn_bwd_f32(const FfnBwdArgs& a) {
       MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
                          static_cast<const float*>(a.xp), static_cast<const float*>(a.w_gate),
                          static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets, Gr, Ur,
-                         static_cast<float*>(nullptr));
+                         static_cast<float*>(nullptr), static_cast<const int32_t*>(nullptr));
       G = Gr; U = Ur;
     }
     MOE_LAUNCH("f32_dact", f32_dact_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
                        static_cast<const float*>(a.dyp), static_cast<const float*>(a.w_down), G, U, a.P, a.d, a.f, a.E,
-                       a.offsets, dG, dU);
+                       a.offsets, dG, dU, static_cast<const int32_t*>(nullptr), static_cast<const float*>(nullptr),
+                       static_cast<float*>(nullptr), static_cast<float*>(nullptr));
     MOE_LAUNCH("f32_dx", f32_dx_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream, dG, dU,
                        static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E,
                        a.offsets, static_cast<float*>(a.dxp));
@@ -160,13 +196,84 @@ void ffn_bwd_f32(const FfnBwdArgs& a) {
   // with P == 0 every segment is empty and the kernels only write zeros (dG/dU are not read)
   MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream,
                      static_cast<const float*>(a.dyp), a.d, static_cast<const float*>(a.act), a.f, a.E, a.P, a.offsets,
-                     static_cast<float*>(a.dw_down));
+                     static_cast<float*>(a.dw_down), static_cast<const int32_t*>(nullptr),
+                     static_cast<const int32_t*>(nullptr));
   MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream,
                      static_cast<const float*>(dG), a.f, static_cast<const float*>(a.xp), a.d, a.E, a.P, a.offsets,
-                     static_cast<float*>(a.dw_gate));
+                     static_cast<float*>(a.dw_gate), static_cast<const int32_t*>(nullptr),
+                     static_cast<const int32_t*>(nullptr));
   MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream,
                      static_cast<const float*>(dU), a.f, static_cast<const float*>(a.xp), a.d, a.E, a.P, a.offsets,
-                     static_cast<float*>(a.dw_up));
+                     static_cast<float*>(a.dw_up), static_cast<const int32_t*>(nullptr),
+                     static_cast<const int32_t*>(nullptr));
+}
+
+// ---- the variants that read the layer input / the output gradient by token -------------------------
+// workspace: [256 | row_token P i32 | row_w P f32 | dG | dU | dA_unscaled | act_w | (G | U)], each aligned to 256
+static size_t f32_list_bytes(int P) { return align_up(static_cast<size_t>(P) * 4, 256); }
+size_t ffn_fwd_gather_ws_bytes_f32(int P, int, int, int) { return 256 + f32_list_bytes(P); }
+size_t ffn_bwd_gather_ws_bytes_f32(int P, int d, int f, int E, int have_saved) {
+  (void)d; (void)E;
+  const size_t pf = align_up(static_cast<size_t>(P) * f * sizeof(float), 256);
+  return 256 + 2 * f32_list_bytes(P) + (have_saved ? 4 : 6) * pf;
+}
+
+void ffn_fwd_gather_f32(const FfnFwdGatherArgs& a) {
+  if (a.P == 0) return;
+  const size_t pf = static_cast<size_t>(a.P) * a.f, pd = static_cast<size_t>(a.P) * a.d;
+  int32_t* row_token = reinterpret_cast<int32_t*>(static_cast<char*>(a.ws) + 256);
+  MOE_LAUNCH("f32_row_token", f32_row_token_kernel, dim3(blocks_for(a.P)), dim3(kF32Threads), 0, a.stream, a.pair_of_row,
+             static_cast<const float*>(nullptr), a.P, a.T, a.k, row_token, static_cast<float*>(nullptr));
+  MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
+             static_cast<const float*>(a.x), static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d, a.f,
+             a.E, a.offsets, static_cast<float*>(a.g_save), static_cast<float*>(a.u_save), static_cast<float*>(a.act),
+             static_cast<const int32_t*>(row_token));
+  MOE_LAUNCH("f32_down", f32_down_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(a.act),
+             static_cast<const float*>(a.w_down), a.P, a.d, a.f, a.E, a.offsets, static_cast<float*>(a.yp));
+}
+
+void ffn_bwd_gather_f32(const FfnBwdGatherArgs& a) {
+  const size_t pf = static_cast<size_t>(a.P) * a.f, pd = static_cast<size_t>(a.P) * a.d;
+  const size_t pf_bytes = align_up(pf * sizeof(float), 256), lb = f32_list_bytes(a.P);
+  char* ws = static_cast<char*>(a.ws) + 256;
+  int32_t* row_token = reinterpret_cast<int32_t*>(ws);
+  float* row_w = reinterpret_cast<float*>(ws + lb);
+  char* big = ws + 2 * lb;
+  float* dG = reinterpret_cast<float*>(big);
+  float* dU = reinterpret_cast<float*>(big + pf_bytes);
+  float* dA = reinterpret_cast<float*>(big + 2 * pf_bytes);
+  float* act_w = reinterpret_cast<float*>(big + 3 * pf_bytes);
+  const float* G = static_cast<const float*>(a.g_save);
+  const float* U = static_cast<const float*>(a.u_save);
+  if (a.P > 0) {
+    MOE_LAUNCH("f32_row_token", f32_row_token_kernel, dim3(blocks_for(a.P)), dim3(kF32Threads), 0, a.stream, a.pair_of_row,
+               a.topk_w, a.P, a.T, a.k, row_token, row_w);
+    if (!G) {   // recompute the pre-activations
+      float* Gr = reinterpret_cast<float*>(big + 4 * pf_bytes);
+      float* Ur = reinterpret_cast<float*>(big + 5 * pf_bytes);
+      MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
+                 static_cast<const float*>(a.x), static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d,
+                 a.f, a.E, a.offsets, Gr, Ur, static_cast<float*>(nullptr), static_cast<const int32_t*>(row_token));
+      G = Gr; U = Ur;
+    }
+    MOE_LAUNCH("f32_dact", f32_dact_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(a.dy),
+               static_cast<const float*>(a.w_down), G, U, a.P, a.d, a.f, a.E, a.offsets, dG, dU,
+               static_cast<const int32_t*>(row_token), static_cast<const float*>(row_w), dA, act_w);
+    MOE_LAUNCH("f32_dw", f32_dw_kernel, dim3(blocks_for(a.P)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(dA), G, U,
+               a.P, a.f, a.pair_of_row, a.dtopk_w);
+    MOE_LAUNCH("f32_dx", f32_dx_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream, dG, dU,
+               static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets,
+               static_cast<float*>(a.dxp));
+  }
+  const size_t per = static_cast<size_t>(a.d) * a.f * a.E;
+  const int32_t* none = nullptr;
+  const int32_t* rt = row_token;
+  MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(a.dy), a.d,
+             static_cast<const float*>(act_w), a.f, a.E, a.P, a.offsets, static_cast<float*>(a.dw_down), rt, none);
+  MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(dG), a.f,
+             static_cast<const float*>(a.x), a.d, a.E, a.P, a.offsets, static_cast<float*>(a.dw_gate), none, rt);
+  MOE_LAUNCH("f32_wgrad", f32_wgrad_kernel, dim3(blocks_for(per)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(dU), a.f,
+             static_cast<const float*>(a.x), a.d, a.E, a.P, a.offsets, static_cast<float*>(a.dw_up), none, rt);
 }
 
 // ---- router linear, fp32 element type: one thread per output, sequential FMA ----------------------

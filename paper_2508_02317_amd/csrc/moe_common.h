@@ -112,6 +112,39 @@ struct FfnBwdArgs {
   void* ws;
   hipStream_t stream;
 };
+// the variants that read the layer input / the output gradient by token (P == T * k)
+struct FfnFwdGatherArgs {
+  const void* x;                      // [T, d]
+  int T, k;
+  const int32_t* pair_of_row;         // [P]
+  const void *w_gate, *w_up, *w_down;
+  int P, d, f, E;
+  const int32_t* offsets;
+  void *g_save, *u_save, *act, *yp;   // g_save/u_save may be null
+  void* ws;
+  hipStream_t stream;
+};
+struct FfnBwdGatherArgs {
+  const void *dy, *x;                 // [T, d]
+  int T, k;
+  const float* topk_w;                // [T, k]
+  const int32_t* pair_of_row;         // [P]
+  const void *g_save, *u_save, *w_gate, *w_up, *w_down;
+  int P, d, f, E;
+  const int32_t* offsets;
+  void *dxp, *dw_gate, *dw_up, *dw_down;
+  float* dtopk_w;                     // [T, k]
+  void* ws;
+  hipStream_t stream;
+};
+size_t ffn_fwd_gather_ws_bytes_bf16(int P, int d, int f, int E);
+size_t ffn_bwd_gather_ws_bytes_bf16(int P, int d, int f, int E, int have_saved);
+void ffn_fwd_gather_bf16(const FfnFwdGatherArgs& a);
+void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a);
+size_t ffn_fwd_gather_ws_bytes_f32(int P, int d, int f, int E);
+size_t ffn_bwd_gather_ws_bytes_f32(int P, int d, int f, int E, int have_saved);
+void ffn_fwd_gather_f32(const FfnFwdGatherArgs& a);
+void ffn_bwd_gather_f32(const FfnBwdGatherArgs& a);
 size_t ffn_fwd_ws_bytes_bf16(int P, int d, int f, int E);
 size_t ffn_bwd_ws_bytes_bf16(int P, int d, int f, int E, int have_saved);
 void ffn_fwd_bf16(const FfnFwdArgs& a);

@@ -273,7 +273,8 @@ extern "C" int32_t moe_permute(const void* x, int dtype, int T, int d, int E, in
   MOE_REQUIRE(E > 0 && k <= E, MOE_ERR_INVALID_ARG, "permute: need E > 0 and k <= E (E=%d k=%d)", E, k);
   MOE_REQUIRE(E <= kMaxExperts, MOE_ERR_UNSUPPORTED, "permute: E=%d above the built maximum %d", E, kMaxExperts);
   if (T == 0) return MOE_OK;
-  MOE_REQUIRE(x && topk_idx && offsets && xp && row_of_pair && pair_of_row, MOE_ERR_INVALID_ARG, "permute: null pointer");
+  MOE_REQUIRE(topk_idx && offsets && row_of_pair && pair_of_row, MOE_ERR_INVALID_ARG, "permute: null pointer");
+  MOE_REQUIRE((x == nullptr) == (xp == nullptr), MOE_ERR_INVALID_ARG, "permute: x and xp must both be given, or both be null for the maps alone");
   MOE_REQUIRE(aligned16(x) && aligned16(xp), MOE_ERR_INVALID_ARG, "permute: x / xp must be 16-byte aligned");
   size_t hist_off = 0;
   const size_t need = permute_ws_layout(T, E, k, &hist_off);
@@ -283,10 +284,10 @@ extern "C" int32_t moe_permute(const void* x, int dtype, int T, int d, int E, in
   const int nchunks = ceil_div(P, kChunkPairs);
   int32_t* rank = static_cast<int32_t*>(ws);
   int32_t* hist = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + hist_off);
-  const int n16 = d * elem_size(dtype) / 16;
+  const int n16 = x ? d * elem_size(dtype) / 16 : 0;     // no rows to copy: the gather kernel only writes the two maps
   MOE_LAUNCH("permute_rank", permute_rank_kernel, dim3(nchunks), dim3(kChunkPairs), 0, s, topk_idx, P, E, nchunks, rank, hist);
   MOE_LAUNCH("permute_scan", permute_scan_kernel, dim3(ceil_div(E, 4)), dim3(256), 0, s, hist, nchunks, E, offsets);
-  MOE_LAUNCH("permute_gather", permute_gather_kernel, dim3(ceil_div(T, kMoverThreads / 64)), dim3(kMoverThreads), 0, s,
+  MOE_LAUNCH(x ? "permute_gather" : "permute_maps", permute_gather_kernel, dim3(ceil_div(T, kMoverThreads / 64)), dim3(kMoverThreads), 0, s,
                      static_cast<const uint4*>(x), T, k, E, n16, topk_idx, rank, hist, nchunks,
                      static_cast<uint4*>(xp), row_of_pair, pair_of_row);
   return check_launch("moe_permute");

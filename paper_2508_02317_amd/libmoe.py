@@ -25,6 +25,8 @@ EXPORTS = [
     "moe_permute_workspace_bytes", "moe_permute",
     "moe_grouped_gemm_swiglu_fwd_workspace_bytes", "moe_grouped_gemm_swiglu_fwd",
     "moe_grouped_gemm_swiglu_bwd_workspace_bytes", "moe_grouped_gemm_swiglu_bwd",
+    "moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes", "moe_grouped_gemm_swiglu_fwd_gather",
+    "moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes", "moe_grouped_gemm_swiglu_bwd_gather",
     "moe_unpermute_combine_fwd", "moe_unpermute_combine_bwd",
     "moe_router_logits_workspace_bytes", "moe_router_logits", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
     "moe_profile_enable", "moe_profile_report", "moe_profile_shader_clock",
@@ -70,6 +72,14 @@ def _load():
     lib.moe_grouped_gemm_swiglu_bwd_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
     lib.moe_grouped_gemm_swiglu_bwd.restype = ctypes.c_int32
     lib.moe_grouped_gemm_swiglu_bwd.argtypes = [vp] * 8 + [i32] * 5 + [vp] * 6 + [sz, vp]
+    lib.moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes.restype = sz
+    lib.moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.moe_grouped_gemm_swiglu_fwd_gather.restype = ctypes.c_int32
+    lib.moe_grouped_gemm_swiglu_fwd_gather.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes.restype = sz
+    lib.moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.moe_grouped_gemm_swiglu_bwd_gather.restype = ctypes.c_int32
+    lib.moe_grouped_gemm_swiglu_bwd_gather.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.moe_unpermute_combine_fwd.restype = ctypes.c_int32
     lib.moe_unpermute_combine_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.moe_unpermute_combine_bwd.restype = ctypes.c_int32
@@ -203,18 +213,25 @@ def moe_route_topk_bwd(dw, topk_w, topk_idx, logits, E, renorm=1, out=None):
 
 
 def moe_permute(x, topk_idx, offsets, E, out=None, ws=None):
-    """-> xp [P,d], row_of_pair [P] i32, pair_of_row [P] i32."""
-    _need(x, None, "x"); _need(topk_idx, torch.int32, "topk_idx"); _need(offsets, torch.int32, "offsets")
-    T, d = x.shape
-    k = topk_idx.shape[1]
+    """-> xp [P,d], row_of_pair [P] i32, pair_of_row [P] i32.  x None: only the two maps (xp is None)."""
+    _need(topk_idx, torch.int32, "topk_idx"); _need(offsets, torch.int32, "offsets")
+    T, k = topk_idx.shape
     P = T * k
+    dev = topk_idx.device
+    if x is not None:
+        _need(x, None, "x")
+        d = x.shape[1]
+    else:
+        d = 8
     if out is None:
-        out = (torch.empty((P, d), dtype=x.dtype, device=x.device), torch.empty(P, dtype=torch.int32, device=x.device),
-               torch.empty(P, dtype=torch.int32, device=x.device))
+        out = (torch.empty((P, d), dtype=x.dtype, device=dev) if x is not None else None,
+               torch.empty(P, dtype=torch.int32, device=dev), torch.empty(P, dtype=torch.int32, device=dev))
     xp, row_of_pair, pair_of_row = out
-    ws, nbytes = _ws(lib.moe_permute_workspace_bytes(T, E, k), ws, x.device)
-    _check(lib.moe_permute(_ptr(x), _dtype_code(x), T, d, E, k, _ptr(topk_idx), _ptr(offsets), _ptr(xp),
-                           _ptr(row_of_pair), _ptr(pair_of_row), _ptr(ws), nbytes, _stream()))
+    if x is None:
+        xp = None
+    ws, nbytes = _ws(lib.moe_permute_workspace_bytes(T, E, k), ws, dev)
+    _check(lib.moe_permute(_ptr(x), _dtype_code(x) if x is not None else MOE_BF16, T, d, E, k, _ptr(topk_idx), _ptr(offsets),
+                           _ptr(xp), _ptr(row_of_pair), _ptr(pair_of_row), _ptr(ws), nbytes, _stream()))
     return xp, row_of_pair, pair_of_row
 
 
@@ -253,6 +270,51 @@ def moe_grouped_gemm_swiglu_bwd(dyp, xp, g_save, u_save, act, w_gate, w_up, w_do
                                            _ptr(w_up), _ptr(w_down), code, P, d, f, E, _ptr(offsets), _ptr(dxp),
                                            _ptr(dwg), _ptr(dwu), _ptr(dwd), _ptr(ws), nbytes, _stream()))
     return dxp, dwg, dwu, dwd
+
+
+def moe_grouped_gemm_swiglu_fwd_gather(x, k, pair_of_row, w_gate, w_up, w_down, offsets, save_gu=True, out=None, ws=None):
+    """Forward without xp: rows are read as x[pair_of_row[r] // k].  -> act [P,f], yp [P,d], g_save, u_save."""
+    _need(x, None, "x"); _need(pair_of_row, torch.int32, "pair_of_row"); _need(offsets, torch.int32, "offsets")
+    for name, w in (("w_gate", w_gate), ("w_up", w_up), ("w_down", w_down)):
+        _need(w, x.dtype, name)
+    T, d = x.shape
+    P = T * k
+    E, f, _ = w_gate.shape
+    dev = x.device
+    if out is None:
+        mk = lambda *s: torch.empty(s, dtype=x.dtype, device=dev)
+        out = (mk(P, f), mk(P, d), mk(P, f) if save_gu else None, mk(P, f) if save_gu else None)
+    act, yp, g, u = out
+    code = _dtype_code(x)
+    ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(code, P, d, f, E), ws, dev)
+    _check(lib.moe_grouped_gemm_swiglu_fwd_gather(_ptr(x), T, k, _ptr(pair_of_row), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                                  code, P, d, f, E, _ptr(offsets), _ptr(g), _ptr(u), _ptr(act), _ptr(yp),
+                                                  _ptr(ws), nbytes, _stream()))
+    return act, yp, g, u
+
+
+def moe_grouped_gemm_swiglu_bwd_gather(dy, x, topk_w, pair_of_row, g_save, u_save, w_gate, w_up, w_down, offsets,
+                                       out=None, ws=None):
+    """Combine backward and FFN backward without dyp / xp.
+    -> dxp [P,d], dw_gate [E,f,d], dw_up [E,f,d], dw_down [E,d,f], dtopk_w [T,k] f32."""
+    _need(dy, x.dtype, "dy"); _need(x, None, "x"); _need(topk_w, torch.float32, "topk_w")
+    _need(pair_of_row, torch.int32, "pair_of_row"); _need(offsets, torch.int32, "offsets")
+    T, d = x.shape
+    k = topk_w.shape[1]
+    P = T * k
+    E, f, _ = w_gate.shape
+    if out is None:
+        out = (torch.empty((P, d), dtype=x.dtype, device=x.device), torch.empty_like(w_gate), torch.empty_like(w_up),
+               torch.empty_like(w_down), torch.empty((T, k), dtype=torch.float32, device=x.device))
+    dxp, dwg, dwu, dwd, dtw = out
+    code = _dtype_code(x)
+    have_saved = int(g_save is not None)
+    ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(code, P, d, f, E, have_saved), ws, x.device)
+    _check(lib.moe_grouped_gemm_swiglu_bwd_gather(_ptr(dy), _ptr(x), T, k, _ptr(topk_w), _ptr(pair_of_row), _ptr(g_save),
+                                                  _ptr(u_save), _ptr(w_gate), _ptr(w_up), _ptr(w_down), code, P, d, f, E,
+                                                  _ptr(offsets), _ptr(dxp), _ptr(dwg), _ptr(dwu), _ptr(dwd), _ptr(dtw),
+                                                  _ptr(ws), nbytes, _stream()))
+    return dxp, dwg, dwu, dwd, dtw
 
 
 def moe_unpermute_combine_fwd(yp, topk_w, row_of_pair, T, k, out=None):

@@ -4,8 +4,10 @@
 A step is one forward + backward pass of the whole path (route, permute, grouped SwiGLU
 GEMMs, combine and their backward: every library call of paper_2508_02317_amd.layer) over
 one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+By default the token rows are gathered inside the grouped products (no expert-ordered copies);
+--no-gather times the path with the separate permute / combine-backward launches instead.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--no-gather]
 
 Workloads are the five configurations of paper_2508_02317_amd.inputs.CONFIGS; the default
 is the 30B-A3B-class layer on one 8K-token micro-batch ("a3b_8k").
@@ -81,6 +83,10 @@ def main():
     ap.add_argument("--router", action="store_true",
                     help="start from hidden states: the router linear and its backward are part of the step "
                          "(the default step starts from given logits, as the metric's path does)")
+    ap.add_argument("--no-gather", action="store_true",
+                    help="call moe_permute, moe_grouped_gemm_swiglu_fwd/bwd and moe_unpermute_combine_bwd separately, "
+                         "writing the expert-ordered copies xp and dyp (the default step uses the *_gather entry points, "
+                         "which read the layer input and the output gradient by token inside the products)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -132,7 +138,7 @@ def main():
         assert not prerouted, "--router needs a workload that routes"
         w_router = dev(np.ascontiguousarray(inp["Wr"].T))             # [E, d]
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, wg, wu, wd, renorm=cfg.renorm, prerouted=prerouted,
-                     save_gu=not args.no_save_gu, w_router=w_router)
+                     save_gu=not args.no_save_gu, w_router=w_router, gather=not args.no_gather)
     P = layer.P
     print("[bench] %s: inputs ready in %.1f s" % (cfg.name, time.time() - t0), file=sys.stderr, flush=True)
 
@@ -245,6 +251,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "k": cfg.k, "f": cfg.f, "P": P,
                    "renorm": cfg.renorm, "save_gu": not args.no_save_gu, "router_linear_in_step": bool(args.router), "hip_graph": bool(args.graph),
+                   "gather_in_gemm": not args.no_gather,
                    "kernel_events": ("every %dth timed step" % sample_every) if events_in_timed_region else "second pass",
                    "unit_note": "routed rows/s" if prerouted else "tokens/s"},
         "roofline": roofline,

@@ -30,17 +30,24 @@ PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (
 
 # HBM bytes per launch (read + write) from the `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this
 # command summarised under profiles/, each counter scaled by what it reads for a plain 1 GiB copy
-# (fetch x 2.000, write x 1.000).  Keyed by (workload, kernel); absent = not measured.
+# (fetch x 2.000, write x 1.000).  Keyed by (workload, kernel, rows gathered inside the products); absent = not measured.
 MEASURED_TRAFFIC = {
-    ("a3b_8k", "ffn_gate_up"): 2229.1e6 + 302.0e6,
-    ("a3b_8k", "ffn_down"): 721.6e6 + 268.4e6,
-    ("a3b_8k", "ffn_dact"): 963.9e6 + 201.3e6,
-    ("a3b_8k", "ffn_dx"): 1881.2e6 + 268.4e6,
-    ("a3b_8k", "wgrad_down"): 376.8e6 + 402.7e6,
-    ("a3b_8k", "wgrad_gate_up"): 503.1e6 + 805.3e6,
-    ("a3b_8k", "permute_gather"): 35.2e6 + 270.1e6,
-    ("a3b_8k", "combine_fwd"): 270.1e6 + 33.6e6,
-    ("a3b_8k", "combine_bwd"): 315.0e6 + 268.7e6,
+    ("a3b_8k", "ffn_gate_up", True): 2223.7e6 + 302.0e6,
+    ("a3b_8k", "ffn_down", True): 713.5e6 + 268.4e6,
+    ("a3b_8k", "ffn_dact", True): 945.4e6 + 303.8e6,
+    ("a3b_8k", "ffn_dx", True): 1864.3e6 + 268.4e6,
+    ("a3b_8k", "wgrad_down", True): 367.6e6 + 402.7e6,
+    ("a3b_8k", "wgrad_gate_up", True): 528.4e6 + 805.3e6,
+    ("a3b_8k", "combine_fwd", True): 270.1e6 + 33.6e6,
+    ("a3b_8k", "ffn_gate_up", False): 2222.3e6 + 302.0e6,
+    ("a3b_8k", "ffn_down", False): 713.4e6 + 268.4e6,
+    ("a3b_8k", "ffn_dact", False): 964.7e6 + 201.3e6,
+    ("a3b_8k", "ffn_dx", False): 1891.2e6 + 268.4e6,
+    ("a3b_8k", "wgrad_down", False): 376.8e6 + 402.7e6,
+    ("a3b_8k", "wgrad_gate_up", False): 501.6e6 + 805.3e6,
+    ("a3b_8k", "permute_gather", False): 35.2e6 + 270.1e6,
+    ("a3b_8k", "combine_fwd", False): 270.1e6 + 33.6e6,
+    ("a3b_8k", "combine_bwd", False): 314.8e6 + 268.7e6,
 }
 
 
@@ -232,7 +239,7 @@ def main():
     dk = kernels[dominant]
     roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
                 "unit": dk["unit"], "frac": dk["frac"], "avg_ms": dk["avg_ms"],
-                "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant))}
+                "traffic": MEASURED_TRAFFIC.get((cfg.name, dominant, not args.no_gather))}
     if "shader_clock_mhz" in dk:
         roofline["shader_clock_mhz"] = dk["shader_clock_mhz"]
     # everything the two grouped-GEMM entry points launch: the products, the device-side schedules and the

@@ -31,6 +31,7 @@
 // the same skeleton with a single segment of all rows.
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 #include "moe_common.h"
 
 namespace moe {
@@ -284,7 +285,7 @@ __device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::N
 #pragma unroll
     for (int ni = 0; ni < T::NI; ++ni)
       if (mi * T::NI + ni >= FROM && mi * T::NI + ni < TO)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[mi][ni], 0, 0, 0);   // transposed tile, see Strip
 }
 
 // acc += sum over segments of A_s(BM x K) * B_s(BN x K)^T for this wave's sub-tile (segments differ
@@ -437,26 +438,46 @@ struct MainLoop {
   }
 };
 
-// element i (0..15) of a 32x32 MFMA tile held by `lane`: row 8*(i/4) + 4*(lane/32) + i%4, col lane%32
-__device__ __forceinline__ int acc_row(int lane, int i) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
-
 // ---- epilogue: accumulators -> LDS (fp32) -> 16-byte row-contiguous global accesses -----------------
-// The MFMA result layout gives a lane one column and four consecutive rows; written out directly
-// that means 2-byte accesses.  Each wave instead parks a 32-row strip of its sub-tile in its own
-// quarter of the (now idle) LDS ring and reads it back row-major, 8 consecutive columns per lane.
+// The products are accumulated transposed (mma() hands the MFMA the weight-side fragment as its first
+// operand): of the 32x32 tile (mi, ni) a lane then holds tile row lane%32 and, for g = 0..3, the four
+// consecutive columns 8g + 4*(lane/32) .. +3 in elements 4g .. 4g+3.  Each wave parks a 32-row strip of its
+// sub-tile in its own quarter of the (now idle) LDS ring with 16-byte writes -- 4 per MFMA tile instead of
+// 16 four-byte ones; a wave can have only 15 LDS operations outstanding and the other workgroup of the CU
+// keeps the LDS busy, so the number of operations is what the epilogue costs -- and reads it back
+// row-major, 8 consecutive columns per lane.
 template <class T> struct Strip {
-  static constexpr int LD = T::WN + 8;                 // floats per staged row: 4 rows shift the banks by 32
+  static constexpr int LD = T::WN + 4;                 // floats per staged row: consecutive rows shift the banks by 4, so the 16 lanes
+                                                       // the LDS serves per cycle (16 rows, 16 bytes each) cover all 64 banks
   static constexpr int kBytes = 32 * LD * 4;
   static_assert(T::kWaves * kBytes <= T::kLdsBytes, "staging strips must fit in the LDS ring");
+  static_assert(LD % 64 == 4, "bank rotation of the parked rows");
 };
 
 template <class T>
 __device__ __forceinline__ void park_strip(const f32x16 (&acc_mi)[T::NI], float* strip, int lane) {
+  float* row = strip + (lane & 31) * Strip<T>::LD + 4 * (lane >> 5);
 #pragma unroll
   for (int ni = 0; ni < T::NI; ++ni)
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-      strip[acc_row(lane, i) * Strip<T>::LD + ni * 32 + (lane & 31)] = acc_mi[ni][i];
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<float4*>(row + ni * 32 + 8 * g) =
+          make_float4(acc_mi[ni][4 * g], acc_mi[ni][4 * g + 1], acc_mi[ni][4 * g + 2], acc_mi[ni][4 * g + 3]);
+}
+
+// sum over each aligned group of LANES (8 or 16) consecutive lanes, left in every lane of the group; data-parallel
+// primitives (register moves between lanes), fixed order of additions
+template <int LANES>
+__device__ __forceinline__ float row_group_sum(float v) {
+  static_assert(LANES == 8 || LANES == 16, "groups of 8 or 16 lanes");
+  auto dpp = [](float x, auto ctrl) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xF, 0xF, true));
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});          // quad_perm [1,0,3,2]
+  v += dpp(v, std::integral_constant<int, 0x4E>{});          // quad_perm [2,3,0,1]
+  v += dpp(v, std::integral_constant<int, 0x141>{});         // row_half_mirror: the other quad of the 8 lanes
+  if constexpr (LANES == 16) v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror: the other 8 lanes
+  return v;
 }
 
 __device__ __forceinline__ void read8(const float* p, float (&v)[8]) {
@@ -637,26 +658,31 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     constexpr int LPR = HW / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
     const int cl = wn * HW + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
+    // All LDS reads of a strip are issued before the first is used: one LDS latency per strip, not per pass
+    // (the other workgroup of the CU keeps the LDS busy, so that latency is several hundred cycles).
+    constexpr int NP = 32 / RPP;                       // passes per strip
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       if (mi >= mi_n) break;
       park_strip<T>(acc[mi], strip, lane);
-      if (cl < ncols) {
+      float g[NP][8], u[NP][8];
 #pragma unroll
-        for (int pass = 0; pass < 32 / RPP; ++pass) {
-          const int rs = pass * RPP + lane / LPR;
-          const int r = wm * WM + mi * 32 + rs;
-          if (r < rows) {
-            float g[8], u[8], a[8];
-            read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, g);
-            read8(strip + rs * Strip<T>::LD + WN / 2 + (lane % LPR) * 8, u);
+      for (int pass = 0; pass < NP; ++pass) {
+        const int rs = pass * RPP + lane / LPR;
+        read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, g[pass]);
+        read8(strip + rs * Strip<T>::LD + WN / 2 + (lane % LPR) * 8, u[pass]);
+      }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) a[q] = g[q] * sigmoid_fast(g[q]) * u[q];
-            const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
-            if (p.out0) store16(p.out0 + o, pack8(g));
-            if (p.out1) store16(p.out1 + o, pack8(u));
-            if (p.out2) store16(p.out2 + o, pack8(a));
-          }
+      for (int pass = 0; pass < NP; ++pass) {
+        const int r = wm * WM + mi * 32 + pass * RPP + lane / LPR;
+        if (cl < ncols && r < rows) {
+          float a[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) a[q] = g[pass][q] * sigmoid_fast(g[pass][q]) * u[pass][q];
+          const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+          if (p.out0) store16(p.out0 + o, pack8(g[pass]));
+          if (p.out1) store16(p.out1 + o, pack8(u[pass]));
+          if (p.out2) store16(p.out2 + o, pack8(a));
         }
       }
     }
@@ -696,43 +722,74 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     constexpr int LPR = WN / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
     const int cl = wn * WN + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
-    if constexpr (KIND == kDAct && FUSED) {
+    // All LDS reads of a strip -- and, for the SwiGLU derivative, the loads of the saved G and U of half a
+    // strip -- are issued before the first is used: one latency per batch, not one per pass.
+    constexpr int NP = 32 / RPP;                       // passes per strip
+    if constexpr (KIND == kDAct) {
+      constexpr int CH = NP >= 2 ? NP / 2 : 1;         // passes per batch of G / U loads
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) {
         if (mi >= mi_n) break;
         park_strip<T>(acc[mi], strip, lane);
 #pragma unroll
-        for (int pass = 0; pass < 32 / RPP; ++pass) {
-          const int rs = pass * RPP + lane / LPR;
-          const int r = wm * WM + mi * 32 + rs;
-          const bool live = cl < ncols && r < rows;
-          float part = 0.0f;
-          if (live) {
-            float v[8], g[8], u[8], dg[8], du[8], aw[8];
-            read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, v);
-            const long gi = static_cast<long>(row0 + r) * p.N + n0 + cl;
-            unpack8(*reinterpret_cast<const uint4*>(p.g + gi), g);
-            unpack8(*reinterpret_cast<const uint4*>(p.u + gi), u);
-            const float wr = p.row_w[row0 + r];
+        for (int p0 = 0; p0 < NP; p0 += CH) {
+          uint4 gq[CH], uq[CH];
+          float v[CH][8], wr[CH];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-              const float sg = sigmoid_fast(g[q]);
-              const float act = g[q] * sg * u[q];
-              part = fmaf(act, v[q], part);
-              const float da = wr * v[q];
-              dg[q] = da * u[q] * (sg * (1.0f + g[q] * (1.0f - sg)));
-              du[q] = da * (g[q] * sg);
-              aw[q] = wr * act;
-            }
-            const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
-            store16(p.out0 + o, pack8(dg));
-            store16(p.out0 + o + p.N, pack8(du));
-            store16(p.act_w + gi, pack8(aw));
+          for (int c = 0; c < CH; ++c) {               // rows / columns that do not exist read the tile's first element
+            const int r = wm * WM + mi * 32 + (p0 + c) * RPP + lane / LPR;
+            const long gi = static_cast<long>(row0 + (r < rows ? r : 0)) * p.N + n0 + (cl < ncols ? cl : 0);
+            gq[c] = *reinterpret_cast<const uint4*>(p.g + gi);
+            uq[c] = *reinterpret_cast<const uint4*>(p.u + gi);
+            if constexpr (FUSED) wr[c] = p.row_w[row0 + (r < rows ? r : 0)];
           }
-          // the LPR lanes of a row add up their columns; every (column slot, row) is written exactly once
 #pragma unroll
-          for (int o = LPR / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
-          if (r < rows && lane % LPR == 0) p.dw_partial[static_cast<long>(nt * T::WGN + wn) * p.P + row0 + r] = part;
+          for (int c = 0; c < CH; ++c)
+            read8(strip + ((p0 + c) * RPP + lane / LPR) * Strip<T>::LD + (lane % LPR) * 8, v[c]);
+#pragma unroll
+          for (int c = 0; c < CH; ++c) {
+            const int r = wm * WM + mi * 32 + (p0 + c) * RPP + lane / LPR;
+            const bool live = cl < ncols && r < rows;
+            float g[8], u[8], dg[8], du[8];
+            unpack8(gq[c], g);
+            unpack8(uq[c], u);
+            const long gi = static_cast<long>(row0 + r) * p.N + n0 + cl;
+            const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+            if constexpr (FUSED) {
+              float part = 0.0f, aw[8];
+#pragma unroll
+              for (int q = 0; q < 8; ++q) {
+                const float sg = sigmoid_fast(g[q]);
+                const float act = g[q] * sg * u[q];
+                part = fmaf(act, v[c][q], part);
+                const float da = wr[c] * v[c][q];
+                dg[q] = da * u[q] * (sg * (1.0f + g[q] * (1.0f - sg)));
+                du[q] = da * (g[q] * sg);
+                aw[q] = wr[c] * act;
+              }
+              if (live) {
+                store16(p.out0 + o, pack8(dg));
+                store16(p.out0 + o + p.N, pack8(du));
+                store16(p.act_w + gi, pack8(aw));
+              } else {
+                part = 0.0f;
+              }
+              // the LPR lanes of a row add up their columns; every (column slot, row) is written exactly once
+              part = row_group_sum<LPR>(part);
+              if (r < rows && lane % LPR == 0) p.dw_partial[static_cast<long>(nt * T::WGN + wn) * p.P + row0 + r] = part;
+            } else {
+#pragma unroll
+              for (int q = 0; q < 8; ++q) {
+                const float sg = sigmoid_fast(g[q]);
+                dg[q] = v[c][q] * u[q] * (sg * (1.0f + g[q] * (1.0f - sg)));
+                du[q] = v[c][q] * (g[q] * sg);
+              }
+              if (live) {
+                store16(p.out0 + o, pack8(dg));
+                store16(p.out0 + o + p.N, pack8(du));
+              }
+            }
+          }
         }
       }
       return;
@@ -741,44 +798,29 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     for (int mi = 0; mi < MI; ++mi) {
       if (mi >= mi_n) break;
       park_strip<T>(acc[mi], strip, lane);
-      if (cl < ncols) {
+      float v[NP][8];
 #pragma unroll
-        for (int pass = 0; pass < 32 / RPP; ++pass) {
-          const int rs = pass * RPP + lane / LPR;
-          const int r = wm * WM + mi * 32 + rs;
-          if (r < rows) {
-            float v[8];
-            read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, v);
-            if constexpr (KIND == kDAct) {
-              const long gi = static_cast<long>(row0 + r) * p.N + n0 + cl;
-              float g[8], u[8], dg[8], du[8];
-              unpack8(*reinterpret_cast<const uint4*>(p.g + gi), g);
-              unpack8(*reinterpret_cast<const uint4*>(p.u + gi), u);
+      for (int pass = 0; pass < NP; ++pass)
+        read8(strip + (pass * RPP + lane / LPR) * Strip<T>::LD + (lane % LPR) * 8, v[pass]);
 #pragma unroll
-              for (int q = 0; q < 8; ++q) {
-                const float sg = sigmoid_fast(g[q]);
-                dg[q] = v[q] * u[q] * (sg * (1.0f + g[q] * (1.0f - sg)));
-                du[q] = v[q] * (g[q] * sg);
-              }
-              const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
-              store16(p.out0 + o, pack8(dg));
-              store16(p.out0 + o + p.N, pack8(du));
-            } else if constexpr (KIND == kRouterFwd) {
-              float* o = p.out_f32 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
-              store16(o, v[0], v[1], v[2], v[3]);
-              store16(o + 4, v[4], v[5], v[6], v[7]);
-            } else if constexpr (KIND == kRouterDx) {
-              bf16_t* o = p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
-              if (p.accumulate) {
-                float old[8];
-                unpack8(*reinterpret_cast<const uint4*>(o), old);
+      for (int pass = 0; pass < NP; ++pass) {
+        const int r = wm * WM + mi * 32 + pass * RPP + lane / LPR;
+        if (cl < ncols && r < rows) {
+          if constexpr (KIND == kRouterFwd) {
+            float* o = p.out_f32 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+            store16(o, v[pass][0], v[pass][1], v[pass][2], v[pass][3]);
+            store16(o + 4, v[pass][4], v[pass][5], v[pass][6], v[pass][7]);
+          } else if constexpr (KIND == kRouterDx) {
+            bf16_t* o = p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
+            if (p.accumulate) {
+              float old[8];
+              unpack8(*reinterpret_cast<const uint4*>(o), old);
 #pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] += old[q];
-              }
-              store16(o, pack8(v));
-            } else {
-              store16(p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl, pack8(v));
+              for (int q = 0; q < 8; ++q) v[pass][q] += old[q];
             }
+            store16(o, pack8(v[pass]));
+          } else {
+            store16(p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl, pack8(v[pass]));
           }
         }
       }
@@ -937,27 +979,27 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   constexpr int RPP = 64 / LPR;
   const int cl = wn * WN + (lane % LPR) * 8;
   float* part = slot >= 0 ? p.partial + static_cast<long>(slot) * p.M * p.N : nullptr;
+  constexpr int NP = 32 / RPP;                         // passes per strip; all their LDS reads are issued before the first is used
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     park_strip<T>(acc[mi], strip, lane);
-    if (cl < ncols) {
+    float v[NP][8];
 #pragma unroll
-      for (int pass = 0; pass < 32 / RPP; ++pass) {
-        const int rs = pass * RPP + lane / LPR;
-        const int rl = wm * WM + mi * 32 + rs;
-        if (rl < mrows) {
-          float v[8];
-          read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, v);
-          const int m = m0 + rl;
-          if (part) {
-            float* o = part + static_cast<long>(m) * p.N + n0 + cl;
-            store16(o, v[0], v[1], v[2], v[3]);
-            store16(o + 4, v[4], v[5], v[6], v[7]);
-          } else {
-            bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
-                                        : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
-            store16(out + n0 + cl, pack8(v));
-          }
+    for (int pass = 0; pass < NP; ++pass)
+      read8(strip + (pass * RPP + lane / LPR) * Strip<T>::LD + (lane % LPR) * 8, v[pass]);
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass) {
+      const int rl = wm * WM + mi * 32 + pass * RPP + lane / LPR;
+      if (cl < ncols && rl < mrows) {
+        const int m = m0 + rl;
+        if (part) {
+          float* o = part + static_cast<long>(m) * p.N + n0 + cl;
+          store16(o, v[pass][0], v[pass][1], v[pass][2], v[pass][3]);
+          store16(o + 4, v[pass][4], v[pass][5], v[pass][6], v[pass][7]);
+        } else {
+          bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
+                                      : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
+          store16(out + n0 + cl, pack8(v[pass]));
         }
       }
     }

@@ -516,7 +516,8 @@ struct RowTiles {
 
 __global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __restrict__ offsets, int E, int P,
                                                                 int bm, RowTiles rt) {
-  __shared__ int32_t scan[kMaxExperts];
+  __shared__ int32_t scan[kMaxExperts];     // inclusive scan of the row tiles per expert
+  __shared__ int32_t first_row[kMaxExperts];
   const int e = threadIdx.x;
   if (e < 64) rt.zeros[e] = 0u;
   int begin = 0, end = 0, nt = 0;
@@ -526,6 +527,7 @@ __global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __
     nt = (end - begin + bm - 1) / bm;
   }
   scan[e] = nt;
+  first_row[e] = begin;
   __syncthreads();
   for (int o = 1; o < 1024; o <<= 1) {
     int v = e >= o ? scan[e - o] : 0;
@@ -534,12 +536,19 @@ __global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __
     __syncthreads();
   }
   // offsets that are not a monotone scan ending at P cannot overflow the lists
-  const int first = scan[e] - nt;
-  for (int i = 0; i < nt && first + i < rt.max_tiles; ++i) {
-    rt.expert[first + i] = e;
-    rt.row0[first + i] = begin + i * bm;
+  const int total = min(scan[1023], rt.max_tiles);
+  // every thread writes the tiles t, t + 1024, ...: the expert of tile t is the first whose inclusive scan exceeds t
+  for (int t = threadIdx.x; t < total; t += 1024) {
+    int lo = 0, hi = E - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (scan[mid] > t) hi = mid; else lo = mid + 1;
+    }
+    const int before = lo > 0 ? scan[lo - 1] : 0;
+    rt.expert[t] = lo;
+    rt.row0[t] = first_row[lo] + (t - before) * bm;
   }
-  if (e == 1023) rt.count[0] = min(scan[1023], rt.max_tiles);
+  if (e == 1023) rt.count[0] = total;
 }
 
 // workgroup id -> virtual tile id such that consecutive virtual ids share an XCD

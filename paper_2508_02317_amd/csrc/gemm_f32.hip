@@ -82,18 +82,20 @@ __global__ __launch_bounds__(kF32Threads) void f32_dact_kernel(
 }
 
 // gradient of the combine weights: dw[pair_of_row[r]] = <dy[token(r)] Wd, act[r]> = <dy[token(r)], yp[r]>
+// one wavefront per row, lanes stride over the columns
 __global__ __launch_bounds__(kF32Threads) void f32_dw_kernel(
     const float* __restrict__ dA_unscaled, const float* __restrict__ G, const float* __restrict__ U, int P, int f,
     const int32_t* __restrict__ pair_of_row, float* __restrict__ dw) {
-  const int r = blockIdx.x * kF32Threads + threadIdx.x;
+  const int r = blockIdx.x * (kF32Threads / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (r >= P) return;
   float s = 0.0f;
-  for (int n = 0; n < f; ++n) {
+  for (int n = lane; n < f; n += 64) {
     const size_t i = static_cast<size_t>(r) * f + n;
     const float g = G[i];
     s = fmaf(g * sigmoid_acc(g) * U[i], dA_unscaled[i], s);
   }
-  dw[min(max(pair_of_row[r], 0), P - 1)] = s;
+  s = wave_sum(s);
+  if (lane == 0) dw[min(max(pair_of_row[r], 0), P - 1)] = s;
 }
 
 __global__ __launch_bounds__(kF32Threads) void f32_row_token_kernel(const int32_t* __restrict__ pair_of_row, const float* __restrict__ topk_w,
@@ -259,7 +261,7 @@ void ffn_bwd_gather_f32(const FfnBwdGatherArgs& a) {
     MOE_LAUNCH("f32_dact", f32_dact_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(a.dy),
                static_cast<const float*>(a.w_down), G, U, a.P, a.d, a.f, a.E, a.offsets, dG, dU,
                static_cast<const int32_t*>(row_token), static_cast<const float*>(row_w), dA, act_w);
-    MOE_LAUNCH("f32_dw", f32_dw_kernel, dim3(blocks_for(a.P)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(dA), G, U,
+    MOE_LAUNCH("f32_dw", f32_dw_kernel, dim3(blocks_for(static_cast<size_t>(a.P) * 64)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(dA), G, U,
                a.P, a.f, a.pair_of_row, a.dtopk_w);
     MOE_LAUNCH("f32_dx", f32_dx_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream, dG, dU,
                static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets,

@@ -22,12 +22,14 @@ def say(msg):
     print(msg, flush=True, file=sys.stderr)
 
 
-def _run(cfg, inp, X, routing=None):
+def _run(cfg, inp, X, routing=None, gather=True):
+    """gather=True is the call sequence bench.py times by default (rows read by token inside the products);
+    gather=False the one with the separate permute / combine-backward launches (bench.py --no-gather)."""
     import torch
     from paper_2508_02317_amd.layer import MoELayer
     dt = cfg.dtype
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), to_dev(inp["Wg"], dt), to_dev(inp["Wu"], dt),
-                     to_dev(inp["Wd"], dt), renorm=cfg.renorm, prerouted=routing is not None)
+                     to_dev(inp["Wd"], dt), renorm=cfg.renorm, prerouted=routing is not None, gather=gather)
     x, dy = to_dev(X, dt), to_dev(inp["dY"], dt)
     if routing is None:
         logits = to_dev(inp["logits"])
@@ -73,12 +75,12 @@ def _check_sampled(cfg, inp, X, layer, idx, w, logits, tokens, experts):
         assert v <= tol, "%s: %.3e > %.1e" % (key, v, tol)
 
 
-@pytest.mark.parametrize("name", ["a3b_8k", "a3b_long"])
-def test_full_size_layer(name):
+@pytest.mark.parametrize("name,gather", [("a3b_8k", True), ("a3b_8k", False), ("a3b_long", True), ("a3b_long", False)])
+def test_full_size_layer(name, gather):
     cfg = CONFIGS[name]
-    say("full size %s: T=%d P=%d" % (name, cfg.T, cfg.P))
+    say("full size %s: T=%d P=%d gather=%s" % (name, cfg.T, cfg.P, gather))
     inp = make_inputs(cfg)
-    layer = _run(cfg, inp, inp["X"])
+    layer = _run(cfg, inp, inp["X"], gather=gather)
     idx, w, counts, offsets = O.route_topk(inp["logits"], cfg.k, cfg.renorm)
     assert np.array_equal(to_np(layer.topk_idx), idx)
     assert np.array_equal(to_np(layer.counts), counts)
@@ -87,17 +89,19 @@ def test_full_size_layer(name):
     row_of_pair, pair_of_row = O.permute_maps(idx, offsets)
     assert np.array_equal(to_np(layer.row_of_pair), row_of_pair)
     assert np.array_equal(to_np(layer.pair_of_row), pair_of_row)
-    # permuted rows are bit copies (sampled rows)
-    xp = to_np(layer.xp)
     r = np.random.default_rng(cfg.seed)
     rows = r.choice(cfg.P, size=256, replace=False)
-    assert np.array_equal(xp[rows], inp["X"][pair_of_row[rows] // cfg.k])
+    if gather:
+        assert layer.xp is None and layer.dyp is None              # no copies in expert order
+    else:
+        assert np.array_equal(to_np(layer.xp)[rows], inp["X"][pair_of_row[rows] // cfg.k])   # bit copies (sampled rows)
     tokens = sorted(r.choice(cfg.T, size=12, replace=False).tolist()) + [0, cfg.T - 1]
     experts = [int(np.argmax(counts)), int(np.argmin(counts))]
     _check_sampled(cfg, inp, inp["X"], layer, idx, w, inp["logits"], tokens, experts)
 
 
-def test_full_size_ep_share_skewed():
+@pytest.mark.parametrize("gather", [True, False])
+def test_full_size_ep_share_skewed(gather):
     cfg = CONFIGS["a3b_ep_skew"]
     say("full size a3b_ep_skew: rows=%d local experts=%d" % (cfg.T, cfg.E))
     inp = make_inputs(cfg)
@@ -110,7 +114,7 @@ def test_full_size_ep_share_skewed():
     assert len(tok) == cfg.T
     lw32 = lw.astype(np.float32)
     X = inp["X"][tok]
-    layer = _run(cfg, inp, X, routing=(lidx, lw32))
+    layer = _run(cfg, inp, X, routing=(lidx, lw32), gather=gather)
     counts, offsets = O.counts_offsets(lidx, cfg.E)
     say("  local counts: %s" % counts.tolist())
     assert np.array_equal(to_np(layer.counts), counts) and np.array_equal(to_np(layer.offsets), offsets)
@@ -135,7 +139,7 @@ def test_full_size_block_from_hidden_states():
     dt = cfg.dtype
     Wr = np.ascontiguousarray(inp["Wr"].T)                           # [E, d]
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), to_dev(inp["Wg"], dt), to_dev(inp["Wu"], dt),
-                     to_dev(inp["Wd"], dt), renorm=cfg.renorm, w_router=to_dev(Wr, dt))
+                     to_dev(inp["Wd"], dt), renorm=cfg.renorm, w_router=to_dev(Wr, dt), gather=True)
     layer.forward(to_dev(inp["X"], dt))
     layer.backward(to_dev(inp["dY"], dt))
     torch.cuda.synchronize()

@@ -514,8 +514,7 @@ struct RowTiles {
   uint32_t* zeros;       // [64] block of zeros the GEMM kernels read for out-of-range reduction indices
 };
 
-__global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __restrict__ offsets, int E, int P,
-                                                                int bm, RowTiles rt) {
+__device__ __forceinline__ void build_row_tiles(const int32_t* __restrict__ offsets, int E, int P, int bm, RowTiles rt) {
   __shared__ int32_t scan[kMaxExperts];     // inclusive scan of the row tiles per expert
   __shared__ int32_t first_row[kMaxExperts];
   const int e = threadIdx.x;
@@ -549,6 +548,10 @@ __global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __
     rt.row0[t] = first_row[lo] + (t - before) * bm;
   }
   if (e == 1023) rt.count[0] = total;
+}
+__global__ __launch_bounds__(1024) void build_row_tiles_kernel(const int32_t* __restrict__ offsets, int E, int P,
+                                                                int bm, RowTiles rt) {
+  build_row_tiles(offsets, E, P, bm, rt);
 }
 
 // workgroup id -> virtual tile id such that consecutive virtual ids share an XCD
@@ -860,8 +863,7 @@ struct WgradItems {
   int max_items, max_split, max_slots;
 };
 
-__global__ __launch_bounds__(1024) void build_wgrad_items_kernel(const int32_t* __restrict__ offsets, int E, int P,
-                                                                  int chunk_rows, WgradItems it) {
+__device__ __forceinline__ void build_wgrad_items(const int32_t* __restrict__ offsets, int E, int P, int chunk_rows, WgradItems it) {
   __shared__ int32_t cnt[kMaxExperts];      // rows per expert
   __shared__ int32_t order[kMaxExperts];    // expert at each rank (descending size, ties by index)
   __shared__ int32_t scan_items[kMaxExperts];
@@ -920,6 +922,43 @@ __global__ __launch_bounds__(1024) void build_wgrad_items_kernel(const int32_t* 
     it.count[0] = min(scan_items[1023], it.max_items);
     it.count[1] = min(scan_split[1023], it.max_split);
   }
+}
+__global__ __launch_bounds__(1024) void build_wgrad_items_kernel(const int32_t* __restrict__ offsets, int E, int P,
+                                                                  int chunk_rows, WgradItems it) {
+  build_wgrad_items(offsets, E, P, chunk_rows, it);
+}
+
+// entries of padding behind the list of row tokens: the scalar loads that run one slab ahead never leave it
+constexpr int kRowTokenPad = 256;
+
+// Everything a pass needs before its first product, in one launch: block 0 builds the (expert, row tile)
+// list, block 1 the weight-gradient work items (backward only), the remaining blocks expand pair_of_row into
+// the token (and combine weight) of every expert-ordered row (gathered passes only).
+struct ScheduleArgs {
+  const int32_t* offsets; int E, P;
+  int bm; RowTiles rt;
+  int chunk_rows; WgradItems items;      // chunk_rows == 0: no weight-gradient items
+  const int32_t* pair_of_row;            // null: no row lists
+  const float* topk_w; int T, k;
+  int32_t* row_token; float* row_w;      // row_w may be null
+};
+__global__ __launch_bounds__(1024) void build_schedules_kernel(ScheduleArgs a) {
+  if (blockIdx.x == 0) {
+    build_row_tiles(a.offsets, a.E, a.P, a.bm, a.rt);
+  } else if (blockIdx.x == 1) {
+    if (a.chunk_rows > 0) build_wgrad_items(a.offsets, a.E, a.P, a.chunk_rows, a.items);
+  } else {
+    const int r = (blockIdx.x - 2) * 1024 + threadIdx.x;
+    if (r >= a.P + kRowTokenPad) return;
+    if (r >= a.P) { a.row_token[r] = 0; return; }
+    const int pair = min(max(a.pair_of_row[r], 0), a.P - 1);
+    a.row_token[r] = min(pair / a.k, a.T - 1);
+    if (a.row_w) a.row_w[r] = a.topk_w[pair];
+  }
+}
+static void launch_schedules(const ScheduleArgs& a, hipStream_t s) {
+  const int blocks = 2 + (a.pair_of_row ? ceil_div(a.P + kRowTokenPad, 1024) : 0);
+  MOE_LAUNCH("build_schedules", build_schedules_kernel, dim3(blocks), dim3(1024), 0, s, a);
 }
 
 struct WgradArgs {
@@ -1241,7 +1280,13 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
   bf16_t* dgu = reinterpret_cast<bf16_t*>(base + w.dgu);       // [P, 2f] = [dG | dU]
   const bf16_t* G = static_cast<const bf16_t*>(a.g_save);
   const bf16_t* U = static_cast<const bf16_t*>(a.u_save);
-  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, row_bm(), rt);
+  const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
+  {
+    ScheduleArgs sa{};
+    sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = row_bm(); sa.rt = rt;
+    sa.chunk_rows = wgrad_chunk_rows(a.P); sa.items = items;
+    launch_schedules(sa, a.stream);
+  }
   if (recompute) {
     bf16_t* Gr = reinterpret_cast<bf16_t*>(base + w.g);
     bf16_t* Ur = reinterpret_cast<bf16_t*>(base + w.u);
@@ -1257,10 +1302,7 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
     launch_row<kDAct>(p, a.P, a.E, a.stream);
   }
   launch_dx(dgu, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.dxp, a.stream);   // dxp = dG Wg + dU Wu
-  const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
   float* partial = reinterpret_cast<float*>(base + w.partial);
-  MOE_LAUNCH("build_wgrad_items", build_wgrad_items_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P,
-             wgrad_chunk_rows(a.P), items);
   {  // dWd[e] = dyp^T act
     WgradArgs p{};
     p.lhs = static_cast<const bf16_t*>(a.dyp); p.ld_lhs = a.d; p.M = a.d;
@@ -1289,18 +1331,6 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
 // row-indexed lists; the list of tokens is padded so that the scalar loads that run one slab ahead of the
 // weight-gradient products never leave it.
 // ============================================================================================
-constexpr int kRowTokenPad = 256;
-
-__global__ __launch_bounds__(256) void build_row_token_kernel(const int32_t* __restrict__ pair_of_row, const float* __restrict__ topk_w,
-                                                               int P, int T, int k, int32_t* __restrict__ row_token,
-                                                               float* __restrict__ row_w) {
-  const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= P + kRowTokenPad) return;
-  if (r >= P) { row_token[r] = 0; return; }
-  const int pair = min(max(pair_of_row[r], 0), P - 1);
-  row_token[r] = min(pair / k, T - 1);
-  if (row_w) row_w[r] = topk_w[pair];
-}
 
 // dw[pair_of_row[r]] = sum over the column slots, in slot order, of the partial dot products of row r
 __global__ __launch_bounds__(256) void finish_dw_kernel(const float* __restrict__ partial, int slots, int P,
@@ -1340,9 +1370,12 @@ void ffn_fwd_gather_bf16(const FfnFwdGatherArgs& a) {
   const GatherWs g = gather_ws(w, a.P, a.f, false);
   const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
   int32_t* row_token = reinterpret_cast<int32_t*>(static_cast<char*>(a.ws) + g.row_token);
-  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, TileRow::BM, rt);
-  MOE_LAUNCH("build_row_token", build_row_token_kernel, dim3(ceil_div(a.P + kRowTokenPad, 256)), dim3(256), 0, a.stream,
-             a.pair_of_row, static_cast<const float*>(nullptr), a.P, a.T, a.k, row_token, static_cast<float*>(nullptr));
+  {
+    ScheduleArgs sa{};
+    sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = TileRow::BM; sa.rt = rt;
+    sa.pair_of_row = a.pair_of_row; sa.T = a.T; sa.k = a.k; sa.row_token = row_token;
+    launch_schedules(sa, a.stream);
+  }
   launch_gate_up(a.x, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.g_save, a.u_save, a.act, a.stream, row_token);
   launch_down(a.act, a.w_down, a.P, a.d, a.f, a.E, a.offsets, rt, a.yp, a.stream);
 }
@@ -1360,9 +1393,14 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
   float* dw_partial = reinterpret_cast<float*>(base + gw.dw_partial);
   const bf16_t* G = static_cast<const bf16_t*>(a.g_save);
   const bf16_t* U = static_cast<const bf16_t*>(a.u_save);
-  MOE_LAUNCH("build_row_tiles", build_row_tiles_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P, TileRow::BM, rt);
-  MOE_LAUNCH("build_row_token", build_row_token_kernel, dim3(ceil_div(a.P + kRowTokenPad, 256)), dim3(256), 0, a.stream,
-             a.pair_of_row, a.topk_w, a.P, a.T, a.k, row_token, row_w);
+  const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
+  {
+    ScheduleArgs sa{};
+    sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = TileRow::BM; sa.rt = rt;
+    sa.chunk_rows = wgrad_chunk_rows(a.P); sa.items = items;
+    sa.pair_of_row = a.pair_of_row; sa.topk_w = a.topk_w; sa.T = a.T; sa.k = a.k; sa.row_token = row_token; sa.row_w = row_w;
+    launch_schedules(sa, a.stream);
+  }
   if (recompute) {
     bf16_t* Gr = reinterpret_cast<bf16_t*>(base + w.g);
     bf16_t* Ur = reinterpret_cast<bf16_t*>(base + w.u);
@@ -1382,10 +1420,7 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
     MOE_LAUNCH("finish_dw", finish_dw_kernel, dim3(ceil_div(a.P, 256)), dim3(256), 0, a.stream, dw_partial, dw_slots(a.f), a.P,
                a.pair_of_row, a.dtopk_w);
   launch_dx(dgu, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.dxp, a.stream);
-  const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
   float* partial = reinterpret_cast<float*>(base + w.partial);
-  MOE_LAUNCH("build_wgrad_items", build_wgrad_items_kernel, dim3(1), dim3(1024), 0, a.stream, a.offsets, a.E, a.P,
-             wgrad_chunk_rows(a.P), items);
   {  // dWd[e] = dy[token]^T (w act)
     WgradArgs p{};
     p.lhs = static_cast<const bf16_t*>(a.dy); p.ld_lhs = a.d; p.M = a.d;

@@ -134,7 +134,10 @@ template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma 
   static constexpr int NR = N * KPC;                         // k-strided: reduction rows per wave and slab (consecutive)
   const char* base[N];       // wave-uniform
   uint32_t voff[N];          // per lane, bytes
-  int kidx[N];               // per lane: reduction index inside the slab of this lane's piece
+  uint32_t kpack[(N + 3) / 4];   // per lane: reduction index inside the slab of this lane's piece of chunk i, 8 bits each
+                                 // (only the partial last slab needs it: packed to keep registers for the main loop)
+  __device__ __forceinline__ void set_kidx(int i, int k) { kpack[i / 4] |= static_cast<uint32_t>(k) << (8 * (i % 4)); }
+  __device__ __forceinline__ int kidx(int i) const { return static_cast<int>((kpack[i / 4] >> (8 * (i % 4))) & 255u); }
   long step;                 // bytes per slab (uniform)
   // gathered k-strided operand: the memory rows of the wave's NR reduction rows of the next slab to be
   // issued, fetched with scalar loads one slab ahead (they do not touch the vector-memory counter
@@ -156,6 +159,9 @@ template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma 
     const bf16_t* const h0 = op.half[0];                     // scalars, so that the selects below stay selects
     const bf16_t* const h1 = op.half[1];
     const int v0 = op.valid[0], v1 = op.valid[1];
+    static_assert(BK <= 256, "reduction indices are packed in 8 bits");
+#pragma unroll
+    for (int i = 0; i < (N + 3) / 4; ++i) kpack[i] = 0u;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int c = wave * N + i;                            // wave-uniform
@@ -181,7 +187,7 @@ template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma 
           const bool own_row = own_base && rh < valid;
           voff[i] = static_cast<uint32_t>((own_row ? static_cast<long>(rh) * op.ld : 0) * 2 + piece * 16);
         }
-        kidx[i] = piece * 8;
+        set_kidx(i, piece * 8);
       } else {
         constexpr int PPK = ROWS / 8;
         const int k = c * KPC + lane / PPK;
@@ -195,10 +201,19 @@ template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma 
         base[i] = reinterpret_cast<const char*>(h0);
         if constexpr (GATHER) voff[i] = static_cast<uint32_t>((ok ? col : 0) * 2);
         else voff[i] = static_cast<uint32_t>(((ok ? col : 0) + static_cast<long>(k) * op.ld) * 2);
-        kidx[i] = k;
+        set_kidx(i, k);
       }
     }
     step = (KS ? (GATHER ? 0L : static_cast<long>(BK) * op.ld) : BK) * 2;
+    // the bases are the same in every lane: say so, to get scalar base + 32-bit lane offset addressing
+    // (no 64-bit per-lane address arithmetic, fewer registers held across the main loop)
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const uint64_t b64 = reinterpret_cast<uint64_t>(base[i]);
+      const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
+      const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
+      base[i] = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+    }
     if constexpr (KS && GATHER) {
       rows = reinterpret_cast<RowList>(reinterpret_cast<uintptr_t>(op.gather + op.grow + wave * NR));
       ld2 = static_cast<uint32_t>(op.ld * 2);
@@ -231,7 +246,7 @@ template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma 
   __device__ __forceinline__ void issue_tail(int slab, int K, const char* zeros, char* tile, int wave) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const bool in_range = slab * BK + kidx[i] < K;
+      const bool in_range = slab * BK + kidx(i) < K;
       const char* g = in_range ? base[i] + slab * step + lane_off(i) : zeros;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                        (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
@@ -571,6 +586,10 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[T::MI][T::NI]) {
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
 }
 
+// Hands back its argument through an empty asm: values derived from the result cannot be computed before
+// this point, so the epilogue's per-lane indices do not occupy registers during the main loop.
+__device__ __forceinline__ int not_before_here(int v) { asm volatile("" : "+v"(v)); return v; }
+
 // ============================================================================================
 // Row-grouped kernels
 // ============================================================================================
@@ -667,26 +686,27 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     { MainLoop<T, false, false, FUSED, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+    const int el = not_before_here(lane);             // this lane, for the epilogue
     constexpr int LPR = HW / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
-    const int cl = wn * HW + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
+    const int cl = wn * HW + (el % LPR) * 8;         // first of this lane's 8 columns inside the tile
     // All LDS reads of a strip are issued before the first is used: one LDS latency per strip, not per pass
     // (the other workgroup of the CU keeps the LDS busy, so that latency is several hundred cycles).
     constexpr int NP = 32 / RPP;                       // passes per strip
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       if (mi >= mi_n) break;
-      park_strip<T>(acc[mi], strip, lane);
+      park_strip<T>(acc[mi], strip, el);
       float g[NP][8], u[NP][8];
 #pragma unroll
       for (int pass = 0; pass < NP; ++pass) {
-        const int rs = pass * RPP + lane / LPR;
-        read8(strip + rs * Strip<T>::LD + (lane % LPR) * 8, g[pass]);
-        read8(strip + rs * Strip<T>::LD + WN / 2 + (lane % LPR) * 8, u[pass]);
+        const int rs = pass * RPP + el / LPR;
+        read8(strip + rs * Strip<T>::LD + (el % LPR) * 8, g[pass]);
+        read8(strip + rs * Strip<T>::LD + WN / 2 + (el % LPR) * 8, u[pass]);
       }
 #pragma unroll
       for (int pass = 0; pass < NP; ++pass) {
-        const int r = wm * WM + mi * 32 + pass * RPP + lane / LPR;
+        const int r = wm * WM + mi * 32 + pass * RPP + el / LPR;
         if (cl < ncols && r < rows) {
           float a[8];
 #pragma unroll
@@ -731,9 +751,10 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     }
 
     float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+    const int el = not_before_here(lane);             // this lane, for the epilogue
     constexpr int LPR = WN / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
-    const int cl = wn * WN + (lane % LPR) * 8;         // first of this lane's 8 columns inside the tile
+    const int cl = wn * WN + (el % LPR) * 8;         // first of this lane's 8 columns inside the tile
     // All LDS reads of a strip -- and, for the SwiGLU derivative, the loads of the saved G and U of half a
     // strip -- are issued before the first is used: one latency per batch, not one per pass.
     constexpr int NP = 32 / RPP;                       // passes per strip
@@ -742,14 +763,14 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) {
         if (mi >= mi_n) break;
-        park_strip<T>(acc[mi], strip, lane);
+        park_strip<T>(acc[mi], strip, el);
 #pragma unroll
         for (int p0 = 0; p0 < NP; p0 += CH) {
           uint4 gq[CH], uq[CH];
           float v[CH][8], wr[CH];
 #pragma unroll
           for (int c = 0; c < CH; ++c) {               // rows / columns that do not exist read the tile's first element
-            const int r = wm * WM + mi * 32 + (p0 + c) * RPP + lane / LPR;
+            const int r = wm * WM + mi * 32 + (p0 + c) * RPP + el / LPR;
             const long gi = static_cast<long>(row0 + (r < rows ? r : 0)) * p.N + n0 + (cl < ncols ? cl : 0);
             gq[c] = *reinterpret_cast<const uint4*>(p.g + gi);
             uq[c] = *reinterpret_cast<const uint4*>(p.u + gi);
@@ -757,10 +778,10 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
           }
 #pragma unroll
           for (int c = 0; c < CH; ++c)
-            read8(strip + ((p0 + c) * RPP + lane / LPR) * Strip<T>::LD + (lane % LPR) * 8, v[c]);
+            read8(strip + ((p0 + c) * RPP + el / LPR) * Strip<T>::LD + (el % LPR) * 8, v[c]);
 #pragma unroll
           for (int c = 0; c < CH; ++c) {
-            const int r = wm * WM + mi * 32 + (p0 + c) * RPP + lane / LPR;
+            const int r = wm * WM + mi * 32 + (p0 + c) * RPP + el / LPR;
             const bool live = cl < ncols && r < rows;
             float g[8], u[8], dg[8], du[8];
             unpack8(gq[c], g);
@@ -788,7 +809,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
               }
               // the LPR lanes of a row add up their columns; every (column slot, row) is written exactly once
               part = row_group_sum<LPR>(part);
-              if (r < rows && lane % LPR == 0) p.dw_partial[static_cast<long>(nt * T::WGN + wn) * p.P + row0 + r] = part;
+              if (r < rows && el % LPR == 0) p.dw_partial[static_cast<long>(nt * T::WGN + wn) * p.P + row0 + r] = part;
             } else {
 #pragma unroll
               for (int q = 0; q < 8; ++q) {
@@ -809,14 +830,14 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       if (mi >= mi_n) break;
-      park_strip<T>(acc[mi], strip, lane);
+      park_strip<T>(acc[mi], strip, el);
       float v[NP][8];
 #pragma unroll
       for (int pass = 0; pass < NP; ++pass)
-        read8(strip + (pass * RPP + lane / LPR) * Strip<T>::LD + (lane % LPR) * 8, v[pass]);
+        read8(strip + (pass * RPP + el / LPR) * Strip<T>::LD + (el % LPR) * 8, v[pass]);
 #pragma unroll
       for (int pass = 0; pass < NP; ++pass) {
-        const int r = wm * WM + mi * 32 + pass * RPP + lane / LPR;
+        const int r = wm * WM + mi * 32 + pass * RPP + el / LPR;
         if (cl < ncols && r < rows) {
           if constexpr (KIND == kRouterFwd) {
             float* o = p.out_f32 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
@@ -1023,21 +1044,22 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   { MainLoop<T, true, true, GA, GB> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, acc); }
 
   float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+  const int el = not_before_here(lane);               // this lane, for the epilogue
   constexpr int LPR = WN / 8;
   constexpr int RPP = 64 / LPR;
-  const int cl = wn * WN + (lane % LPR) * 8;
+  const int cl = wn * WN + (el % LPR) * 8;
   float* part = slot >= 0 ? p.partial + static_cast<long>(slot) * p.M * p.N : nullptr;
   constexpr int NP = 32 / RPP;                         // passes per strip; all their LDS reads are issued before the first is used
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    park_strip<T>(acc[mi], strip, lane);
+    park_strip<T>(acc[mi], strip, el);
     float v[NP][8];
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass)
-      read8(strip + (pass * RPP + lane / LPR) * Strip<T>::LD + (lane % LPR) * 8, v[pass]);
+      read8(strip + (pass * RPP + el / LPR) * Strip<T>::LD + (el % LPR) * 8, v[pass]);
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass) {
-      const int rl = wm * WM + mi * 32 + pass * RPP + lane / LPR;
+      const int rl = wm * WM + mi * 32 + pass * RPP + el / LPR;
       if (cl < ncols && rl < mrows) {
         const int m = m0 + rl;
         if (part) {
@@ -1079,26 +1101,28 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
 // ============================================================================================
 // Host side
 // ============================================================================================
-// Tile shapes in use.  Row-grouped products keep the row (token) side at 128 so that experts
-// with a few hundred rows waste little; the weight side is 256 wide.
-typedef Tile<128, 256, 32, 2, 2, 3> TileRow;           // 72 KiB of LDS: two 4-wave workgroups per CU
-typedef Tile<128, 256, 32, 2, 2, 3> TileWgrad;
-typedef Tile<64, 128, 64, 2, 2, 3> TileRouter;         // skinny products with N = E: 72 KiB of LDS, 128-byte row pieces
-typedef Tile<128, 256, 64, 2, 4, 3> TileWide;           // 144 KiB of LDS: one 8-wave workgroup per CU, 64 x 64 per wave, 128-byte row pieces
+// Tile shapes in use.
+//   TileBig (default): 256 x 256 outputs, 64-wide slabs, one 8-wave workgroup per CU (2 x 4 wavefronts of
+//     128 x 64), two stages of 64 KiB.  A slab row is a whole 128-byte line, so the tile needs a third of the
+//     L2 requests per flop of TileRow and two thirds of the bytes; measured inside the layer step it is
+//     3 % faster over the six products of the 30B-class shapes (6 % on the down product, 3.6 % slower on dA).
+//   TileRow (MOE_GEMM_TILE=0 in the environment): 128 x 256, 32-wide slabs, two 4-wave workgroups per CU
+//     (2 x 2 wavefronts of 64 x 128), three stages of 24 KiB each.
+//   TileRouter: 64 x 128 x 64 for the skinny products with N = E, two workgroups per CU.
+typedef Tile<256, 256, 64, 2, 4, 2> TileBig;
+typedef Tile<128, 256, 32, 2, 2, 3> TileRow;
+typedef Tile<64, 128, 64, 2, 2, 3> TileRouter;
 
-// 0 = default.  MOE_GEMM_TILE=1 in the environment selects the 64-wide-slab variant for every product: its
-// 128-byte row pieces halve the number of L2 requests of reduction-contiguous operands (a tuning knob; on the
-// 30B-class shapes it is 3 % faster for the gate/up product and 10-25 % slower for the other five).
 static int tile_choice() {
   static int choice = -1;
   if (choice < 0) {
     const char* s = getenv("MOE_GEMM_TILE");
-    choice = s ? atoi(s) : 0;
+    choice = (s && atoi(s) == 0) ? 0 : 1;
   }
   return choice;
 }
 
-static int row_bm() { return tile_choice() == 1 ? TileWide::BM : TileRow::BM; }
+static int row_bm() { return tile_choice() == 1 ? TileBig::BM : TileRow::BM; }
 // bound used for workspace sizing: the smallest row tile gives the longest list
 static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 
@@ -1196,10 +1220,10 @@ static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
   MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T, FUSED>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);
 }
 
-template <int KIND>
+template <int KIND, bool FUSED = false>
 static void launch_row(const RowArgs& p, int P, int E, hipStream_t s) {
-  if (tile_choice() == 1) launch_row_t<KIND, TileWide>(p, P, E, s);
-  else launch_row_t<KIND, TileRow>(p, P, E, s);
+  if (tile_choice() == 1) launch_row_t<KIND, TileBig, FUSED>(p, P, E, s);
+  else launch_row_t<KIND, TileRow, FUSED>(p, P, E, s);
 }
 
 template <int WHICH, class T, bool GATHER = false>
@@ -1222,10 +1246,10 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
              dim3(256), 0, s, p);
 }
 
-template <int WHICH>
+template <int WHICH, bool GATHER = false>
 static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
-  if (tile_choice() == 1) launch_wgrad_t<WHICH, TileWide>(p, s);
-  else launch_wgrad_t<WHICH, TileWgrad>(p, s);
+  if (tile_choice() == 1) launch_wgrad_t<WHICH, TileBig, GATHER>(p, s);
+  else launch_wgrad_t<WHICH, TileRow, GATHER>(p, s);
 }
 
 // row_token == null: xp is in expert order; else xp is the token-major input and rows are gathered from it
@@ -1239,7 +1263,7 @@ static void launch_gate_up(const void* xp, const void* wg, const void* wu, int P
   p.w_expert_stride = static_cast<long>(f) * d; p.ldw = d;
   p.K = d; p.N = f; p.offsets = offsets; p.P = P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
   p.out0 = static_cast<bf16_t*>(G); p.out1 = static_cast<bf16_t*>(U); p.out2 = static_cast<bf16_t*>(act); p.ldo = f;
-  if (row_token) launch_row_t<kGateUp, TileRow, true>(p, P, E, s);
+  if (row_token) launch_row<kGateUp, true>(p, P, E, s);
   else launch_row<kGateUp>(p, P, E, s);
 }
 
@@ -1342,7 +1366,8 @@ __global__ __launch_bounds__(256) void finish_dw_kernel(const float* __restrict_
   dw[min(max(pair_of_row[r], 0), P - 1)] = s;
 }
 
-static int dw_slots(int f) { return ceil_div(f, TileRow::BN) * TileRow::WGN; }
+// column slots of the partial dot products: one per (column tile, wavefront column) of the dA product
+static int dw_slots(int f) { return tile_choice() == 1 ? ceil_div(f, TileBig::BN) * TileBig::WGN : ceil_div(f, TileRow::BN) * TileRow::WGN; }
 
 struct GatherWs { size_t row_token, row_w, act_w, dw_partial, total; };
 static GatherWs gather_ws(const WsLayout& w, int P, int f, bool bwd) {
@@ -1372,7 +1397,7 @@ void ffn_fwd_gather_bf16(const FfnFwdGatherArgs& a) {
   int32_t* row_token = reinterpret_cast<int32_t*>(static_cast<char*>(a.ws) + g.row_token);
   {
     ScheduleArgs sa{};
-    sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = TileRow::BM; sa.rt = rt;
+    sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = row_bm(); sa.rt = rt;
     sa.pair_of_row = a.pair_of_row; sa.T = a.T; sa.k = a.k; sa.row_token = row_token;
     launch_schedules(sa, a.stream);
   }
@@ -1396,7 +1421,7 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
   const WgradItems items = wgrad_items_at(a.ws, w, a.P, a.E);
   {
     ScheduleArgs sa{};
-    sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = TileRow::BM; sa.rt = rt;
+    sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = row_bm(); sa.rt = rt;
     sa.chunk_rows = wgrad_chunk_rows(a.P); sa.items = items;
     sa.pair_of_row = a.pair_of_row; sa.topk_w = a.topk_w; sa.T = a.T; sa.k = a.k; sa.row_token = row_token; sa.row_w = row_w;
     launch_schedules(sa, a.stream);
@@ -1414,7 +1439,7 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
     p.K = a.d; p.N = a.f; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = dgu; p.ldo = 2L * a.f; p.g = G; p.u = U;
     p.row_token = row_token; p.row_w = row_w; p.act_w = act_w; p.dw_partial = dw_partial;
-    launch_row_t<kDAct, TileRow, true>(p, a.P, a.E, a.stream);
+    launch_row<kDAct, true>(p, a.P, a.E, a.stream);
   }
   if (a.P > 0)
     MOE_LAUNCH("finish_dw", finish_dw_kernel, dim3(ceil_div(a.P, 256)), dim3(256), 0, a.stream, dw_partial, dw_slots(a.f), a.P,
@@ -1428,7 +1453,7 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
     p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_down); p.out1 = p.out0; p.m_split = a.d;
     p.row_token = row_token;
-    launch_wgrad_t<0, TileWgrad, true>(p, a.stream);
+    launch_wgrad<0, true>(p, a.stream);
   }
   {  // [dWg[e]; dWu[e]] = [dG | dU]^T x[token]
     WgradArgs p{};
@@ -1437,7 +1462,7 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
     p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_gate); p.out1 = static_cast<bf16_t*>(a.dw_up); p.m_split = a.f;
     p.row_token = row_token;
-    launch_wgrad_t<1, TileWgrad, true>(p, a.stream);
+    launch_wgrad<1, true>(p, a.stream);
   }
 }
 

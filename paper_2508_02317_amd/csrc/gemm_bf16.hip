@@ -2,14 +2,14 @@
 // (Sec. 3.2.5 SwiGLU among the efficient kernels; App. B.6 stacked expert-major weights).
 //
 // One kernel skeleton serves all nine matrix products of the layer (and the three of the router):
-//   * a BM x BN output tile per 256-thread workgroup: 2 x 2 wavefronts, each owning a
-//     WM x WN sub-tile made of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, fp32
-//     accumulators kept in registers for the whole reduction);
-//   * the reduction dimension is walked in BK-wide slabs through a 3-stage LDS ring that is
-//     filled by direct global->LDS loads (no staging registers); two slabs are in flight
-//     behind the one being multiplied, the MFMA operands are double-buffered in registers one
-//     reduction step ahead, and one barrier per slab separates writers from readers; a partial
-//     last slab reads zeros for the reduction indices it does not have;
+//   * a BM x BN output tile per workgroup, a grid of WGM x WGN wavefronts over it, each owning a
+//     WM x WN sub-tile made of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, fp32 accumulators kept in
+//     registers for the whole reduction); the default is 256 x 256 with 2 x 4 wavefronts of 128 x 64;
+//   * the reduction dimension is walked in BK-wide slabs through an S-stage LDS ring that is
+//     filled by direct global->LDS loads (no staging registers); S-1 slabs are in flight behind the
+//     one being multiplied, the MFMA operands are double-buffered in registers one reduction step
+//     ahead, and one barrier per slab separates writers from readers; a partial last slab reads
+//     zeros for the reduction indices it does not have;
 //   * results leave through LDS as well, so that all global stores (and the loads of the
 //     saved pre-activations in the fused SwiGLU derivative) are 16 bytes per lane and
 //     contiguous along rows;

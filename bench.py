@@ -281,7 +281,7 @@ def cpu_baseline(cfg, inp, Xh, layer, prerouted, routing):
     import numpy as np
     from oracle import moe_oracle as O
     flops_per_token = 18.0 * cfg.d * cfg.f * cfg.k
-    Ts = int(min(cfg.T, max(64, 1.0e12 // flops_per_token)))      # about 1 TFLOP of fp64 work
+    Ts = int(min(cfg.T, max(64, 1.0e13 // flops_per_token)))      # at most 10 TFLOP of fp64 work (about 20 s on 16 host cores)
     X, dY = Xh[:Ts], inp["dY"][:Ts]
     t0 = time.perf_counter()
     if prerouted:

@@ -54,7 +54,14 @@ struct Tile {
   static constexpr int kStageBytes = kABytes + kBBytes;
   static constexpr int kStages = STAGES_;                 // LDS ring: one slab being read, the others in flight
   static constexpr int kLdsBytes = kStages * kStageBytes;
-  static constexpr int kBlocksPerCu = 2 * kLdsBytes <= 160 * 1024 ? 2 : 1;   // by LDS capacity
+  // Epilogue staging strips (one per wave, 32 rows x (WN + 4) floats).  With a two-stage ring and room in the
+  // 160 KiB of LDS they sit behind the first stage, so that stage can already take the first slab of the
+  // workgroup's next tile while the epilogue runs; otherwise they reuse the ring from its start.
+  static constexpr int kStripBytes = 32 * (WN + 4) * 4;
+  static constexpr bool kStripsBehindStage0 = kStages == 2 && kStageBytes + kWaves * kStripBytes <= 156 * 1024;
+  static constexpr int kStripBase = kStripsBehindStage0 ? kStageBytes : 0;
+  static constexpr int kLdsAlloc = kStripBase + kWaves * kStripBytes > kLdsBytes ? kStripBase + kWaves * kStripBytes : kLdsBytes;
+  static constexpr int kBlocksPerCu = 2 * kLdsAlloc <= 160 * 1024 ? 2 : 1;   // by LDS capacity
   static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4;
 };
 
@@ -90,8 +97,8 @@ __device__ __forceinline__ int ks_off(int k, int piece) {
 
 // ---- MFMA operand fragments ----------------------------------------------------------------------------
 // Fragment = 32 rows x 16 k: lane l holds row l%32, k = 8*(l/32) .. +7 of the 16-wide step kk.
-// frag_off: this lane's byte offset inside the operand tile, computed once per kernel; the main loop
-// only adds compile-time stage offsets, so an LDS read costs no address arithmetic.
+// frag_off: this lane's byte offset inside the operand tile, computed once per kernel for step 0; the main
+// loop derives the other steps with one XOR (or a constant) and adds compile-time stage offsets.
 template <bool KS, int ROWS, int BK>
 __device__ __forceinline__ int frag_off(int row_base, int kk, int lane) {
   if constexpr (!KS) {
@@ -279,18 +286,28 @@ template <class T> struct Frags {
   bf16x8 a[T::MI];
   bf16x8 b[T::NI];
 };
-// per-lane LDS offsets of every fragment and step, relative to the start of a stage
+// per-lane LDS offsets of every fragment at reduction step 0, relative to the start of its operand tile
 template <class T> struct FragOffsets {
-  int a[T::MI][T::BK / 16];
-  int b[T::NI][T::BK / 16];
+  int a[T::MI];
+  int b[T::NI];
 };
+// Offset of the same fragment at step kk (a compile-time constant in the unrolled loop).  k-strided tile: 16
+// reduction rows further, and the swizzle (k & 3) is unchanged.  k-contiguous tile: the step moves the piece
+// index by 2*kk, and because the piece index is XORed with the row's swizzle, so is the offset: one XOR of bits
+// above the 16-byte piece and below the row pitch.  One register per fragment instead of one per (fragment, step).
+template <bool KS, int ROWS, int BK>
+__device__ __forceinline__ int frag_step(int off0, int kk) {
+  static_assert((BK / 16 - 1) * 32 < BK * 2, "the step bits must lie inside a row");
+  if constexpr (KS) return off0 + kk * 16 * ROWS * 2;
+  else return off0 ^ (kk << 5);
+}
 
 template <class T, bool A_KS, bool B_KS>
 __device__ __forceinline__ void load_frags(Frags<T>& f, const char* stage, const FragOffsets<T>& fo, int kk) {
 #pragma unroll
-  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM>(stage + fo.a[i][kk]);
+  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM>(stage + frag_step<A_KS, T::BM, T::BK>(fo.a[i], kk));
 #pragma unroll
-  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN>(stage + T::kABytes + fo.b[i][kk]);
+  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN>(stage + T::kABytes + frag_step<B_KS, T::BN, T::BK>(fo.b[i], kk));
 }
 // MFMAs number FROM .. TO-1 (row-major over the wave's MI x NI fragments) of one reduction step
 template <class T, int FROM, int TO>
@@ -405,23 +422,47 @@ struct MainLoop {
     run_from<0, ACTIVE>(kt, acc);                      // the remaining < S slabs
   }
 
-  __device__ __forceinline__ void run(const Operand* opA, const Operand* opB, int nseg, int K_, char* lds_,
-                                      const bf16_t* zeros_, const int (&a_row)[T::MI], const int (&b_row)[T::NI],
-                                      bool active, f32x16 (&acc)[T::MI][T::NI]) {
+  // reduction length, LDS ring and the per-lane fragment offsets of this wave's sub-tile
+  __device__ __forceinline__ void prepare(int K_, char* lds_, const bf16_t* zeros_, const int (&a_row)[T::MI],
+                                          const int (&b_row)[T::NI]) {
     const int tid = threadIdx.x, lane = tid & 63;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
     lds = lds_; zeros = reinterpret_cast<const char*>(zeros_); K = K_;
+    nfull = K > 0 ? K / T::BK : 0;
+    nslabs = K > 0 ? (K + T::BK - 1) / T::BK : 0;
+#pragma unroll
+    for (int i = 0; i < T::MI; ++i) fo.a[i] = frag_off<A_KS, T::BM, T::BK>(a_row[i], 0, lane);
+#pragma unroll
+    for (int i = 0; i < T::NI; ++i) fo.b[i] = frag_off<B_KS, T::BN, T::BK>(b_row[i], 0, lane);
+  }
+  // enqueue slabs [FIRST, LAST) of a segment into their stages; FIRST == 0 also points the loads at the operands.
+  // The ring must be idle from stage FIRST on.  Slabs are enqueued in order, whatever else the caller does between.
+  template <int FIRST, int LAST>
+  __device__ __forceinline__ void start(const Operand& oa, const Operand& ob) {
+    if constexpr (FIRST == 0) {
+      const int lane = threadIdx.x & 63;
+      da.init(oa, wave, lane);
+      db.init(ob, wave, lane);
+    }
+#pragma unroll
+    for (int s0 = FIRST; s0 < LAST; ++s0)
+      if (s0 < nslabs) issue(s0, s0);
+  }
+  // multiply the segment whose first S slabs have been enqueued
+  __device__ __forceinline__ void go(bool active, f32x16 (&acc)[T::MI][T::NI]) {
+    if (nslabs <= 0) return;
+    wait_slabs_in_flight<L, S - 1>(nslabs - 1);        // slab 0 has landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (active) stream<true>(acc); else stream<false>(acc);
+    __syncthreads();                                   // all reads done before anything refills the ring
+  }
+
+  __device__ __forceinline__ void run(const Operand* opA, const Operand* opB, int nseg, int K_, char* lds_,
+                                      const bf16_t* zeros_, const int (&a_row)[T::MI], const int (&b_row)[T::NI],
+                                      bool active, f32x16 (&acc)[T::MI][T::NI]) {
+    prepare(K_, lds_, zeros_, a_row, b_row);
     if (K <= 0) return;
-    nfull = K / T::BK;
-    nslabs = (K + T::BK - 1) / T::BK;
-#pragma unroll
-    for (int i = 0; i < T::MI; ++i)
-#pragma unroll
-      for (int kk = 0; kk < STEPS; ++kk) fo.a[i][kk] = frag_off<A_KS, T::BM, T::BK>(a_row[i], kk, lane);
-#pragma unroll
-    for (int i = 0; i < T::NI; ++i)
-#pragma unroll
-      for (int kk = 0; kk < STEPS; ++kk) fo.b[i][kk] = frag_off<B_KS, T::BN, T::BK>(b_row[i], kk, lane);
 #pragma nounroll
     for (int seg = 0; seg < nseg; ++seg) {
       Operand oa, ob;                                  // picked field by field: no dynamically indexed copies
@@ -439,16 +480,8 @@ struct MainLoop {
       ob.valid[1] = opB[0].valid[1];
       ob.gather = opB[0].gather;
       ob.grow = opB[0].grow;
-      da.init(oa, wave, lane);
-      db.init(ob, wave, lane);
-#pragma unroll
-      for (int s0 = 0; s0 < S; ++s0)
-        if (s0 < nslabs) issue(s0, s0);
-      wait_slabs_in_flight<L, S - 1>(nslabs - 1);      // slab 0 has landed
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      if (active) stream<true>(acc); else stream<false>(acc);
-      __syncthreads();                                 // all reads done before anything refills the ring
+      start<0, S>(oa, ob);
+      go(active, acc);
     }
   }
 };
@@ -464,8 +497,8 @@ struct MainLoop {
 template <class T> struct Strip {
   static constexpr int LD = T::WN + 4;                 // floats per staged row: consecutive rows shift the banks by 4, so the 16 lanes
                                                        // the LDS serves per cycle (16 rows, 16 bytes each) cover all 64 banks
-  static constexpr int kBytes = 32 * LD * 4;
-  static_assert(T::kWaves * kBytes <= T::kLdsBytes, "staging strips must fit in the LDS ring");
+  static constexpr int kBytes = T::kStripBytes;
+  static_assert(kBytes == 32 * LD * 4 && T::kStripBase + T::kWaves * kBytes <= T::kLdsAlloc, "staging strips must fit in the LDS allocation");
   static_assert(LD % 64 == 4, "bank rotation of the parked rows");
 };
 
@@ -685,7 +718,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     opB.valid[0] = opB.valid[1] = ncols;
     { MainLoop<T, false, false, FUSED, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
-    float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+    float* strip = reinterpret_cast<float*>(lds + T::kStripBase + wave * Strip<T>::kBytes);
     const int el = not_before_here(lane);             // this lane, for the epilogue
     constexpr int LPR = HW / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
@@ -750,7 +783,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       { MainLoop<T, false, true> ml; ml.run(opsA, opsB, 2, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     }
 
-    float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
+    float* strip = reinterpret_cast<float*>(lds + T::kStripBase + wave * Strip<T>::kBytes);
     const int el = not_before_here(lane);             // this lane, for the epilogue
     constexpr int LPR = WN / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
@@ -995,6 +1028,11 @@ struct WgradArgs {
   const int32_t* row_token;    // GATHER kernels: [P + padding], token of each expert-ordered row
 };
 
+// Column tiles one workgroup of a weight-gradient product takes in turn (see the kernel).  Measured in the layer
+// step: two for [dW_gate; dW_up] (7 % faster at 512 rows per expert, no change at 2560), one for dW_down (with two
+// or all three of its column tiles per workgroup it is 15-40 % slower).
+template <class T, int WHICH> constexpr int kWgradSpan = (T::kStripsBehindStage0 && WHICH == 1) ? 2 : 1;
+
 // WHICH 0: dW_down, 1: [dW_gate; dW_up], 2: router (separate symbols so profiles tell them apart).
 // GATHER: the operand that holds one row per token -- lhs for WHICH 0 (the output gradient), rhs for WHICH 1
 // (the layer input) -- is the token-major matrix itself, and reduction row r reads its row row_token[r].
@@ -1004,23 +1042,27 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   constexpr bool GA = GATHER && WHICH == 0, GB = GATHER && WHICH == 1;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   constexpr int BM = T::BM, BN = T::BN, WM = T::WM, WN = T::WN, MI = T::MI, NI = T::NI;
-  const int per_e = p.tiles_m * p.tiles_n;
+  // A workgroup takes kWgradSpan<T, WHICH> column tiles of one (work item, row tile) in turn: they share the lhs
+  // panel, and where the staging strips sit behind the first stage the first slab of the next tile is
+  // already on its way while the epilogue of the current one runs.
+  constexpr int SPAN = kWgradSpan<T, WHICH>;
+  const int spans_n = (p.tiles_n + SPAN - 1) / SPAN;
+  const int per_e = p.tiles_m * spans_n;
   const int n_items = p.items.count[0];
   const int v = xcd_remap(blockIdx.x, per_e * n_items);
   if (v < 0) return;
   ClockStamp stamp(p.clock);
-  const int item = v / per_e, mt = (v % per_e) / p.tiles_n, nt = v % p.tiles_n;
+  const int item = v / per_e, mt = (v % per_e) / spans_n, nt0 = (v % spans_n) * SPAN;
   const int e = p.items.expert[item];
   const int slot = p.items.slot[item];
   if (slot == -2) return;
   const int begin = p.items.k0[item], end = p.items.k1[item];
-  const int m0 = mt * BM, n0 = nt * BN;
-  const int mrows = min(BM, p.M - m0), ncols = min(BN, p.N - n0);
+  const int m0 = mt * BM;
+  const int mrows = min(BM, p.M - m0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / T::WGN, wn = wave % T::WGN;
 
   f32x16 acc[MI][NI];
-  zero_acc<T>(acc);
   int a_row[MI], b_row[NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) a_row[i] = wm * WM + i * 32;
@@ -1035,43 +1077,67 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   opA.gather = GA ? p.row_token : nullptr;
   opA.grow = begin;
   opB.ld = p.ld_rhs;
-  opB.half[0] = p.rhs + (GB ? 0L : static_cast<long>(begin) * p.ld_rhs) + n0;
-  opB.half[1] = opB.half[0] + BN / 2;
-  opB.valid[0] = min(ncols, BN / 2);
-  opB.valid[1] = max(ncols - BN / 2, 0);
   opB.gather = GB ? p.row_token : nullptr;
   opB.grow = begin;
-  { MainLoop<T, true, true, GA, GB> ml; ml.run(&opA, &opB, 1, end - begin, lds, p.zeros, a_row, b_row, true, acc); }
+  auto point_b = [&](int nt) {                         // rhs columns of column tile nt
+    const int n0 = nt * BN, ncols = min(BN, p.N - n0);
+    opB.half[0] = p.rhs + (GB ? 0L : static_cast<long>(begin) * p.ld_rhs) + n0;
+    opB.half[1] = opB.half[0] + BN / 2;
+    opB.valid[0] = min(ncols, BN / 2);
+    opB.valid[1] = max(ncols - BN / 2, 0);
+  };
+  MainLoop<T, true, true, GA, GB> ml;
+  ml.prepare(end - begin, lds, p.zeros, a_row, b_row);
+  point_b(nt0);
+  ml.template start<0, T::kStages>(opA, opB);
 
-  float* strip = reinterpret_cast<float*>(lds + wave * Strip<T>::kBytes);
-  const int el = not_before_here(lane);               // this lane, for the epilogue
+  float* strip = reinterpret_cast<float*>(lds + T::kStripBase + wave * Strip<T>::kBytes);
   constexpr int LPR = WN / 8;
   constexpr int RPP = 64 / LPR;
-  const int cl = wn * WN + (el % LPR) * 8;
   float* part = slot >= 0 ? p.partial + static_cast<long>(slot) * p.M * p.N : nullptr;
   constexpr int NP = 32 / RPP;                         // passes per strip; all their LDS reads are issued before the first is used
+#pragma nounroll
+  for (int t = 0; t < SPAN; ++t) {
+    const int nt = nt0 + t;
+    if (nt >= p.tiles_n) break;
+    const int n0 = nt * BN, ncols = min(BN, p.N - n0);
+    zero_acc<T>(acc);
+    ml.go(true, acc);
+    const bool more = t + 1 < SPAN && nt + 1 < p.tiles_n;
+    if (more) {                                        // the ring is idle: the next tile's first slab(s) can go
+      point_b(nt + 1);
+      if constexpr (T::kStripsBehindStage0) ml.template start<0, 1>(opA, opB);
+    }
+    const int el = not_before_here(lane);             // this lane, for the epilogue
+    const int cl = wn * WN + (el % LPR) * 8;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    park_strip<T>(acc[mi], strip, el);
-    float v[NP][8];
+    for (int mi = 0; mi < MI; ++mi) {
+      park_strip<T>(acc[mi], strip, el);
+      float v[NP][8];
 #pragma unroll
-    for (int pass = 0; pass < NP; ++pass)
-      read8(strip + (pass * RPP + el / LPR) * Strip<T>::LD + (el % LPR) * 8, v[pass]);
+      for (int pass = 0; pass < NP; ++pass)
+        read8(strip + (pass * RPP + el / LPR) * Strip<T>::LD + (el % LPR) * 8, v[pass]);
 #pragma unroll
-    for (int pass = 0; pass < NP; ++pass) {
-      const int rl = wm * WM + mi * 32 + pass * RPP + el / LPR;
-      if (cl < ncols && rl < mrows) {
-        const int m = m0 + rl;
-        if (part) {
-          float* o = part + static_cast<long>(m) * p.N + n0 + cl;
-          store16(o, v[pass][0], v[pass][1], v[pass][2], v[pass][3]);
-          store16(o + 4, v[pass][4], v[pass][5], v[pass][6], v[pass][7]);
-        } else {
-          bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
-                                      : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
-          store16(out + n0 + cl, pack8(v[pass]));
+      for (int pass = 0; pass < NP; ++pass) {
+        const int rl = wm * WM + mi * 32 + pass * RPP + el / LPR;
+        if (cl < ncols && rl < mrows) {
+          const int m = m0 + rl;
+          if (part) {
+            float* o = part + static_cast<long>(m) * p.N + n0 + cl;
+            store16(o, v[pass][0], v[pass][1], v[pass][2], v[pass][3]);
+            store16(o + 4, v[pass][4], v[pass][5], v[pass][6], v[pass][7]);
+          } else {
+            bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
+                                        : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
+            store16(out + n0 + cl, pack8(v[pass]));
+          }
         }
       }
+    }
+    if (more) {
+      __syncthreads();                                 // every wave is done with its strip: the rest of the ring may be refilled
+      if constexpr (T::kStripsBehindStage0) ml.template start<1, T::kStages>(opA, opB);
+      else ml.template start<0, T::kStages>(opA, opB);
     }
   }
 }
@@ -1211,13 +1277,13 @@ static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&row_grouped_kernel<KIND, T, FUSED>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsAlloc);
     attr_set = true;
   }
   p.n_tiles_n = ceil_div(p.N, KIND == kGateUp ? T::BN / 2 : T::BN);
   p.clock = KIND < 4 ? prof_clock_slot(KIND) : nullptr;
   const unsigned grid = padded_grid((ceil_div(P, T::BM) + E) * p.n_tiles_n);
-  MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T, FUSED>), dim3(grid), dim3(T::kThreads), T::kLdsBytes, s, p);
+  MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T, FUSED>), dim3(grid), dim3(T::kThreads), T::kLdsAlloc, s, p);
 }
 
 template <int KIND, bool FUSED = false>
@@ -1231,15 +1297,15 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<WHICH, T, GATHER>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsAlloc);
     attr_set = true;
   }
   p.clock = WHICH < 2 ? prof_clock_slot(4 + WHICH) : nullptr;
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
-  const unsigned grid = padded_grid(p.tiles_m * p.tiles_n * p.items.max_items);
+  const unsigned grid = padded_grid(p.tiles_m * ceil_div(p.tiles_n, kWgradSpan<T, WHICH>) * p.items.max_items);
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T, GATHER>), dim3(grid),
-             dim3(T::kThreads), T::kLdsBytes, s, p);
+             dim3(T::kThreads), T::kLdsAlloc, s, p);
   const long rblocks = (static_cast<long>(p.M) * p.N + 2047) / 2048;
   const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 256L)), static_cast<unsigned>(p.items.max_split));
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down_reduce" : WHICH == 1 ? "wgrad_gate_up_reduce" : "wgrad_router_reduce", wgrad_reduce_kernel, rgrid,

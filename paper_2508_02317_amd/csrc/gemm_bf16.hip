@@ -1052,7 +1052,12 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   const int v = xcd_remap(blockIdx.x, per_e * n_items);
   if (v < 0) return;
   ClockStamp stamp(p.clock);
-  const int item = v / per_e, mt = (v % per_e) / spans_n, nt0 = (v % spans_n) * SPAN;
+  // order of a work item's tiles: row tile fastest for [dW_gate; dW_up] (neighbouring workgroups share the rhs panel;
+  // measured 6 % faster at 512 rows per expert), column span fastest for the others
+  constexpr bool MT_FASTEST = WHICH == 1;
+  const int item = v / per_e;
+  const int mt = MT_FASTEST ? (v % per_e) % p.tiles_m : (v % per_e) / spans_n;
+  const int nt0 = (MT_FASTEST ? (v % per_e) / p.tiles_m : v % spans_n) * SPAN;
   const int e = p.items.expert[item];
   const int slot = p.items.slot[item];
   if (slot == -2) return;

@@ -1049,15 +1049,24 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   const int spans_n = (p.tiles_n + SPAN - 1) / SPAN;
   const int per_e = p.tiles_m * spans_n;
   const int n_items = p.items.count[0];
-  const int v = xcd_remap(blockIdx.x, per_e * n_items);
-  if (v < 0) return;
-  ClockStamp stamp(p.clock);
   // order of a work item's tiles: row tile fastest for [dW_gate; dW_up] (neighbouring workgroups share the rhs panel;
   // measured 6 % faster at 512 rows per expert), column span fastest for the others
   constexpr bool MT_FASTEST = WHICH == 1;
-  const int item = v / per_e;
-  const int mt = MT_FASTEST ? (v % per_e) % p.tiles_m : (v % per_e) / spans_n;
-  const int nt0 = (MT_FASTEST ? (v % per_e) / p.tiles_m : v % spans_n) * SPAN;
+  // Work items come sorted by length, so consecutive stretches of the list differ in work: they are dealt to the
+  // XCDs (workgroup b runs on XCD b % 8) in turn, in units of 1/g of an item's tiles -- whole items while there
+  // are at least 8 per XCD, otherwise g runs of the slow tile index, so that under skewed routing every XCD still
+  // gets several units of the few long items.  A unit's workgroups are consecutive on their XCD (shared panels).
+  const int slow = MT_FASTEST ? spans_n : p.tiles_m;
+  int g = 1;
+  while (g < slow && (n_items * g < 8 * kXcds || slow % g != 0)) ++g;
+  const int per_u = per_e / g;                          // g divides slow, so it divides per_e
+  const int unit = (blockIdx.x / kXcds) / per_u * kXcds + blockIdx.x % kXcds;
+  if (unit >= n_items * g) return;
+  ClockStamp stamp(p.clock);
+  const int item = unit / g;
+  const int vi = (unit % g) * per_u + (blockIdx.x / kXcds) % per_u;   // position among the item's tiles
+  const int mt = MT_FASTEST ? vi % p.tiles_m : vi / spans_n;
+  const int nt0 = (MT_FASTEST ? vi / p.tiles_m : vi % spans_n) * SPAN;
   const int e = p.items.expert[item];
   const int slot = p.items.slot[item];
   if (slot == -2) return;
@@ -1200,8 +1209,10 @@ static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 // Rows per reduction chunk of the weight gradients: long enough that the fp32 partial tiles stay a small
 // part of the traffic, short enough that the largest work item is a small part of the launch.  At most
 // 2 * ceil(P / chunk) <= 64 partial slots can ever be needed (an expert is split only if it has more than
-// one chunk, and the chunks of split experts hold more than half their rows each but the last).
-static int wgrad_chunk_rows(int P) { return std::max(1024, static_cast<int>(align_up(static_cast<size_t>(ceil_div(P, 32)), 256))); }
+// one chunk, and the chunks of split experts hold more than half their rows each but the last).  The floor of
+// 2048 rows is the measured optimum when 16 experts share 16K rows with two thirds of them on one expert
+// (1024: a third more partial traffic; 3072: too few work items per XCD).
+static int wgrad_chunk_rows(int P) { return std::max(2048, static_cast<int>(align_up(static_cast<size_t>(ceil_div(P, 32)), 256))); }
 static int wgrad_max_items(int P, int E, int chunk) { return E + ceil_div(P, chunk); }
 static int wgrad_max_split(int P, int E, int chunk) { return std::max(1, std::min(E, ceil_div(P, chunk))); }
 static int wgrad_max_slots(int P, int chunk) { return 2 * ceil_div(P, chunk); }
@@ -1308,7 +1319,8 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   p.clock = WHICH < 2 ? prof_clock_slot(4 + WHICH) : nullptr;
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
-  const unsigned grid = padded_grid(p.tiles_m * ceil_div(p.tiles_n, kWgradSpan<T, WHICH>) * p.items.max_items);
+  // units are dealt to the XCDs in groups of 8, the last group may be partial: up to 8 more units than items
+  const unsigned grid = padded_grid(p.tiles_m * ceil_div(p.tiles_n, kWgradSpan<T, WHICH>) * (p.items.max_items + kXcds));
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T, GATHER>), dim3(grid),
              dim3(T::kThreads), T::kLdsAlloc, s, p);
   const long rblocks = (static_cast<long>(p.M) * p.N + 2047) / 2048;

@@ -37,7 +37,7 @@ CASES = [
     (64, 1, 128, 128, 4, "bf16", "one_expert"),      # every row on one expert, three empty
     (3, 1, 64, 64, 2, "bf16", "normal"),             # segments of one or two rows
     (130, 3, 72, 40, 6, "f32", "skew"),
-    (2600, 2, 136, 72, 3, "bf16", "skew"),           # experts longer than one weight-gradient chunk (split path)
+    (5300, 2, 136, 72, 3, "bf16", "skew"),           # experts longer than one weight-gradient chunk (split path)
 ]
 
 

@@ -235,11 +235,11 @@ def test_grouped_ffn_fwd_bwd(L, T, k, d, f, E, dt, kind):
 
 
 def test_ffn_bwd_weight_gradients_of_long_experts(L):
-    """Experts with more rows than one reduction chunk (1024 rows here) go through the split path: fp32
+    """Experts with more rows than one reduction chunk (2048 rows here) go through the split path: fp32
     partial tiles per chunk, summed in chunk order.  Counts cover 3.x chunks, exactly one chunk, exactly two
     chunks, one row over a chunk, short and empty experts."""
     dt, d, f = "bf16", 136, 72
-    counts = np.array([3300, 1024, 0, 2048, 1025, 37, 0, 600], dtype=np.int64)
+    counts = np.array([6700, 2048, 0, 4096, 2049, 37, 0, 600], dtype=np.int64)
     E, P = len(counts), int(counts.sum())
     offs = np.zeros(E + 1, dtype=np.int32)
     offs[1:] = np.cumsum(counts)

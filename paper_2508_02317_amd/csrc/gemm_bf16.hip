@@ -513,6 +513,29 @@ __device__ __forceinline__ void park_strip(const f32x16 (&acc_mi)[T::NI], float*
           make_float4(acc_mi[ni][4 * g], acc_mi[ni][4 * g + 1], acc_mi[ni][4 * g + 2], acc_mi[ni][4 * g + 3]);
 }
 
+// The same for results that leave as bf16 with no further arithmetic: rounded before they are parked, so the strip
+// holds 2 instead of 4 bytes per element and the LDS moves half the bytes both ways.  Rows are WN * 2 bytes with
+// no padding; the 16-byte pieces of a row are XORed with the row index, which keeps the row-major 16-byte reads
+// free of bank conflicts (16 lanes = 256 consecutive bytes) and spreads the 32 rows of a parking write over
+// 16 different pieces.
+template <class T>
+__device__ __forceinline__ void park_strip_bf16(const f32x16 (&acc_mi)[T::NI], char* strip, int lane) {
+  constexpr int PPR = T::WN / 8;                       // 16-byte pieces per staged row
+  const int r = lane & 31;
+  char* row = strip + r * (T::WN * 2) + 8 * (lane >> 5);
+#pragma unroll
+  for (int ni = 0; ni < T::NI; ++ni)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<uint2*>(row + (((ni * 4 + g) ^ (r & (PPR - 1))) << 4)) =
+          make_uint2(pack_bf16x2(acc_mi[ni][4 * g], acc_mi[ni][4 * g + 1]), pack_bf16x2(acc_mi[ni][4 * g + 2], acc_mi[ni][4 * g + 3]));
+}
+// 8 consecutive columns (piece `piece` of staged row `row`) of a strip parked by park_strip_bf16
+template <class T>
+__device__ __forceinline__ uint4 read_strip_bf16(const char* strip, int row, int piece) {
+  return *reinterpret_cast<const uint4*>(strip + row * (T::WN * 2) + ((piece ^ (row & (T::WN / 8 - 1))) << 4));
+}
+
 // sum over each aligned group of LANES (8 or 16) consecutive lanes, left in every lane of the group; data-parallel
 // primitives (register moves between lanes), fixed order of additions
 template <int LANES>
@@ -860,6 +883,23 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       }
       return;
     }
+    if constexpr (KIND == kDown || KIND == kDX) {      // rounded and stored as they are: staged as bf16
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        if (mi >= mi_n) break;
+        park_strip_bf16<T>(acc[mi], reinterpret_cast<char*>(strip), el);
+        uint4 v[NP];
+#pragma unroll
+        for (int pass = 0; pass < NP; ++pass)
+          v[pass] = read_strip_bf16<T>(reinterpret_cast<const char*>(strip), pass * RPP + el / LPR, el % LPR);
+#pragma unroll
+        for (int pass = 0; pass < NP; ++pass) {
+          const int r = wm * WM + mi * 32 + pass * RPP + el / LPR;
+          if (cl < ncols && r < rows) store16(p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl, v[pass]);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       if (mi >= mi_n) break;
@@ -876,7 +916,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
             float* o = p.out_f32 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
             store16(o, v[pass][0], v[pass][1], v[pass][2], v[pass][3]);
             store16(o + 4, v[pass][4], v[pass][5], v[pass][6], v[pass][7]);
-          } else if constexpr (KIND == kRouterDx) {
+          } else {                                     // kRouterDx
             bf16_t* o = p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl;
             if (p.accumulate) {
               float old[8];
@@ -885,8 +925,6 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
               for (int q = 0; q < 8; ++q) v[pass][q] += old[q];
             }
             store16(o, pack8(v[pass]));
-          } else {
-            store16(p.out0 + static_cast<long>(row0 + r) * p.ldo + n0 + cl, pack8(v[pass]));
           }
         }
       }
@@ -1124,26 +1162,40 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     }
     const int el = not_before_here(lane);             // this lane, for the epilogue
     const int cl = wn * WN + (el % LPR) * 8;
+    if (part) {                                        // chunk of a split expert: fp32 partial tile
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      park_strip<T>(acc[mi], strip, el);
-      float v[NP][8];
+      for (int mi = 0; mi < MI; ++mi) {
+        park_strip<T>(acc[mi], strip, el);
+        float v[NP][8];
 #pragma unroll
-      for (int pass = 0; pass < NP; ++pass)
-        read8(strip + (pass * RPP + el / LPR) * Strip<T>::LD + (el % LPR) * 8, v[pass]);
+        for (int pass = 0; pass < NP; ++pass)
+          read8(strip + (pass * RPP + el / LPR) * Strip<T>::LD + (el % LPR) * 8, v[pass]);
 #pragma unroll
-      for (int pass = 0; pass < NP; ++pass) {
-        const int rl = wm * WM + mi * 32 + pass * RPP + el / LPR;
-        if (cl < ncols && rl < mrows) {
-          const int m = m0 + rl;
-          if (part) {
-            float* o = part + static_cast<long>(m) * p.N + n0 + cl;
+        for (int pass = 0; pass < NP; ++pass) {
+          const int rl = wm * WM + mi * 32 + pass * RPP + el / LPR;
+          if (cl < ncols && rl < mrows) {
+            float* o = part + static_cast<long>(m0 + rl) * p.N + n0 + cl;
             store16(o, v[pass][0], v[pass][1], v[pass][2], v[pass][3]);
             store16(o + 4, v[pass][4], v[pass][5], v[pass][6], v[pass][7]);
-          } else {
+          }
+        }
+      }
+    } else {                                           // whole expert: rounded once, staged as bf16
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        park_strip_bf16<T>(acc[mi], reinterpret_cast<char*>(strip), el);
+        uint4 v[NP];
+#pragma unroll
+        for (int pass = 0; pass < NP; ++pass)
+          v[pass] = read_strip_bf16<T>(reinterpret_cast<const char*>(strip), pass * RPP + el / LPR, el % LPR);
+#pragma unroll
+        for (int pass = 0; pass < NP; ++pass) {
+          const int rl = wm * WM + mi * 32 + pass * RPP + el / LPR;
+          if (cl < ncols && rl < mrows) {
+            const int m = m0 + rl;
             bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
                                         : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
-            store16(out + n0 + cl, pack8(v[pass]));
+            store16(out + n0 + cl, v[pass]);
           }
         }
       }

@@ -33,21 +33,21 @@ PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (
 # (fetch x 2.000, write x 1.000).  Keyed by (workload, kernel, rows gathered inside the products); absent = not measured.
 MEASURED_TRAFFIC = {
     ("a3b_8k", "combine_fwd", True): 270.1e6 + 33.6e6,
-    ("a3b_8k", "ffn_dact", True): 1020.7e6 + 305.5e6,
-    ("a3b_8k", "ffn_down", True): 648.6e6 + 268.5e6,
-    ("a3b_8k", "ffn_dx", True): 1642.9e6 + 268.5e6,
-    ("a3b_8k", "ffn_gate_up", True): 1527.6e6 + 380.5e6,
-    ("a3b_8k", "wgrad_down", True): 376.2e6 + 402.9e6,
-    ("a3b_8k", "wgrad_gate_up", True): 712.8e6 + 805.5e6,
-    ("a3b_8k", "combine_bwd", False): 315.0e6 + 268.7e6,
+    ("a3b_8k", "ffn_dact", True): 1016.9e6 + 305.5e6,
+    ("a3b_8k", "ffn_down", True): 646.4e6 + 268.5e6,
+    ("a3b_8k", "ffn_dx", True): 1632.6e6 + 268.5e6,
+    ("a3b_8k", "ffn_gate_up", True): 1536.0e6 + 379.2e6,
+    ("a3b_8k", "wgrad_down", True): 389.3e6 + 403.0e6,
+    ("a3b_8k", "wgrad_gate_up", True): 737.0e6 + 805.5e6,
+    ("a3b_8k", "combine_bwd", False): 314.9e6 + 268.7e6,
     ("a3b_8k", "combine_fwd", False): 270.1e6 + 33.6e6,
-    ("a3b_8k", "ffn_dact", False): 1084.1e6 + 201.3e6,
-    ("a3b_8k", "ffn_down", False): 650.2e6 + 268.5e6,
-    ("a3b_8k", "ffn_dx", False): 1642.7e6 + 268.4e6,
-    ("a3b_8k", "ffn_gate_up", False): 1582.1e6 + 380.4e6,
+    ("a3b_8k", "ffn_dact", False): 1082.5e6 + 201.3e6,
+    ("a3b_8k", "ffn_down", False): 647.1e6 + 268.5e6,
+    ("a3b_8k", "ffn_dx", False): 1629.2e6 + 268.5e6,
+    ("a3b_8k", "ffn_gate_up", False): 1585.3e6 + 380.3e6,
     ("a3b_8k", "permute_gather", False): 35.2e6 + 270.1e6,
-    ("a3b_8k", "wgrad_down", False): 388.9e6 + 403.0e6,
-    ("a3b_8k", "wgrad_gate_up", False): 679.2e6 + 805.4e6,
+    ("a3b_8k", "wgrad_down", False): 404.0e6 + 403.4e6,
+    ("a3b_8k", "wgrad_gate_up", False): 726.4e6 + 805.5e6,
 }
 
 

@@ -1209,24 +1209,27 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
 }
 
 // out[e] = bf16( sum over the chunks of a split expert, in chunk order, of its fp32 partial tiles )
+// (the split experts are taken in turn by the same blocks: with balanced routing there are none, and the launch
+// is a few hundred blocks that read one counter and leave)
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
-  const int s = blockIdx.y;
-  if (s >= p.items.count[1]) return;
+  const int n_split = p.items.count[1];
   const long mn = static_cast<long>(p.M) * p.N;
-  const int e = p.items.split_expert[s], n = p.items.split_n[s];
-  const float* part = p.partial + static_cast<long>(p.items.split_slot0[s]) * mn;
-  for (long i = (static_cast<long>(blockIdx.x) * 256 + threadIdx.x) * 8; i < mn; i += static_cast<long>(gridDim.x) * 2048) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int j = 0; j < n; ++j) {
-      float v[8];
-      read8(part + j * mn + i, v);
+  for (int s = 0; s < n_split; ++s) {
+    const int e = p.items.split_expert[s], n = p.items.split_n[s];
+    const float* part = p.partial + static_cast<long>(p.items.split_slot0[s]) * mn;
+    for (long i = (static_cast<long>(blockIdx.x) * 256 + threadIdx.x) * 8; i < mn; i += static_cast<long>(gridDim.x) * 2048) {
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < n; ++j) {
+        float v[8];
+        read8(part + j * mn + i, v);
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[q] += v[q];
+        for (int q = 0; q < 8; ++q) acc[q] += v[q];
+      }
+      const int m = static_cast<int>(i / p.N), col = static_cast<int>(i % p.N);   // N is a multiple of 8: one row
+      bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
+                                  : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
+      store16(out + col, pack8(acc));
     }
-    const int m = static_cast<int>(i / p.N), col = static_cast<int>(i % p.N);   // N is a multiple of 8: one row
-    bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
-                                : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
-    store16(out + col, pack8(acc));
   }
 }
 
@@ -1376,7 +1379,7 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T, GATHER>), dim3(grid),
              dim3(T::kThreads), T::kLdsAlloc, s, p);
   const long rblocks = (static_cast<long>(p.M) * p.N + 2047) / 2048;
-  const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 256L)), static_cast<unsigned>(p.items.max_split));
+  const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 1024L)));
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down_reduce" : WHICH == 1 ? "wgrad_gate_up_reduce" : "wgrad_router_reduce", wgrad_reduce_kernel, rgrid,
              dim3(256), 0, s, p);
 }

@@ -249,6 +249,18 @@ def main():
     gemm_ms = sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in gemm_names)
     gemm_tflops = 18.0 * P * cfg.d * cfg.f / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     gemm_peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+    # forward / backward separately, and the step against the lower of the two roofs: at about 512 rows per expert
+    # the bytes the products cannot avoid (every activation and weight once per product that needs it, the saved
+    # and intermediate tensors once each way, the weight gradients once) take as long at 8 TB/s as the flops at peak
+    fwd_names = [n for n in gemm_names if n.endswith(("gate_up", "down")) and not n.startswith("wgrad")]
+    fwd_ms = sum(kernels[n]["avg_ms"] for n in fwd_names)      # one launch each (a second gate/up launch is the backward's recompute)
+    bwd_ms = gemm_ms - fwd_ms - sum(kernels[n]["avg_ms"] * kernels[n]["launches_per_step"] for n in gemm_names if n.startswith("build_"))
+    es = 2 if cfg.dtype == "bf16" else 4
+    Pd, Pf, Edf = float(P) * cfg.d * es, float(P) * cfg.f * es, float(cfg.E) * cfg.d * cfg.f * es
+    fwd_bytes = 2 * Pd + 2 * Pf + 3 * Edf + (0 if args.no_save_gu else 2 * Pf)      # x, act out + in, yp; weights; G, U
+    bwd_bytes = 3 * Pd + 3 * Pf + 4 * Pf + 6 * Edf      # dy, x, dxp; act, G, U; [dG|dU] out + in; weights in, gradients out
+    hbm_floor_ms = (fwd_bytes + bwd_bytes) / (PEAK_HBM_GBS * 1e9) * 1e3
+    mfma_floor_ms = 18.0 * P * cfg.d * cfg.f / (gemm_peak * 1e12) * 1e3
 
     out = {
         "metric": "MoE layer fwd+bwd tokens/sec on 1 MI355X; grouped-GEMM % of bf16 MFMA peak",
@@ -263,7 +275,11 @@ def main():
                    "unit_note": "routed rows/s" if prerouted else "tokens/s"},
         "roofline": roofline,
         "grouped_gemm": {"tflops": round(gemm_tflops, 2), "frac_of_peak": round(gemm_tflops / gemm_peak, 4),
-                         "peak": gemm_peak, "ms_per_step": round(gemm_ms, 4)},
+                         "peak": gemm_peak, "ms_per_step": round(gemm_ms, 4),
+                         "fwd_tflops": round(6.0 * P * cfg.d * cfg.f / (fwd_ms * 1e-3) / 1e12, 2) if fwd_ms > 0 else None,
+                         "bwd_tflops": round(12.0 * P * cfg.d * cfg.f / (bwd_ms * 1e-3) / 1e12, 2) if bwd_ms > 0 else None,
+                         "mfma_floor_ms": round(mfma_floor_ms, 4), "hbm_floor_ms": round(hbm_floor_ms, 4),
+                         "frac_of_lower_roof": round(max(mfma_floor_ms, hbm_floor_ms) / gemm_ms, 4) if gemm_ms > 0 else None},
         "kernels": kernels,
         "context": PAPER_CONTEXT,
     }

@@ -262,6 +262,7 @@ def main():
     hbm_floor_ms = (fwd_bytes + bwd_bytes) / (PEAK_HBM_GBS * 1e9) * 1e3
     mfma_floor_ms = 18.0 * P * cfg.d * cfg.f / (gemm_peak * 1e12) * 1e3
 
+    working_set = 6 * Edf + 4 * float(cfg.T) * cfg.d * es + 3 * Pd + 6 * Pf
     out = {
         "metric": "MoE layer fwd+bwd tokens/sec on 1 MI355X; grouped-GEMM % of bf16 MFMA peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -272,7 +273,10 @@ def main():
                    "renorm": cfg.renorm, "save_gu": not args.no_save_gu, "router_linear_in_step": bool(args.router), "hip_graph": bool(args.graph),
                    "gather_in_gemm": not args.no_gather,
                    "kernel_events": ("every %dth timed step" % sample_every) if events_in_timed_region else "second pass",
-                   "unit_note": "routed rows/s" if prerouted else "tokens/s"},
+                   "unit_note": "routed rows/s" if prerouted else "tokens/s",
+                   # weights and their gradients, the token-major and the expert-ordered activations: under 256 MB the
+                   # step runs out of the last-level cache and its mover GB/s are not HBM rates
+                   "working_set_mb": round(working_set / 1e6, 1), "cache_resident": bool(working_set < 256e6)},
         "roofline": roofline,
         "grouped_gemm": {"tflops": round(gemm_tflops, 2), "frac_of_peak": round(gemm_tflops / gemm_peak, 4),
                          "peak": gemm_peak, "ms_per_step": round(gemm_ms, 4),

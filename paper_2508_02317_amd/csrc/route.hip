@@ -127,15 +127,16 @@ __global__ __launch_bounds__(1024) void route_scan_kernel(
   }
   __syncthreads();
   // Hillis-Steele inclusive scan over epad (<= 1024) entries
+  const int tid = static_cast<int>(threadIdx.x);
   for (int o = 1; o < epad; o <<= 1) {
     int32_t v = 0;
-    if (threadIdx.x < epad && threadIdx.x >= o) v = scan[threadIdx.x - o];
+    if (tid < epad && tid >= o) v = scan[tid - o];
     __syncthreads();
-    if (threadIdx.x < epad) scan[threadIdx.x] += v;
+    if (tid < epad) scan[tid] += v;
     __syncthreads();
   }
-  if (threadIdx.x < E) offsets[threadIdx.x + 1] = scan[threadIdx.x];
-  if (threadIdx.x == 0) offsets[0] = 0;
+  if (tid < E) offsets[tid + 1] = scan[tid];
+  if (tid == 0) offsets[0] = 0;
 }
 
 // histogram of an already known assignment (pre-routed rows): same per-workgroup rows as above

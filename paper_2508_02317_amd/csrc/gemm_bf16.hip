@@ -811,11 +811,11 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     constexpr int LPR = WN / 8;                        // lanes per output row (8 columns each)
     constexpr int RPP = 64 / LPR;                      // rows per pass
     const int cl = wn * WN + (el % LPR) * 8;         // first of this lane's 8 columns inside the tile
-    // All LDS reads of a strip -- and, for the SwiGLU derivative, the loads of the saved G and U of half a
+    // All LDS reads of a strip -- and, for the SwiGLU derivative, the loads of the saved G and U of the
     // strip -- are issued before the first is used: one latency per batch, not one per pass.
     constexpr int NP = 32 / RPP;                       // passes per strip
     if constexpr (KIND == kDAct) {
-      constexpr int CH = NP >= 2 ? NP / 2 : 1;         // passes per batch of G / U loads
+      constexpr int CH = NP;                           // passes per batch of G / U loads: the whole strip (the fragment registers are free now)
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) {
         if (mi >= mi_n) break;

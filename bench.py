@@ -33,12 +33,12 @@ PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (
 # (fetch x 2.000, write x 1.000).  Keyed by (workload, kernel, rows gathered inside the products); absent = not measured.
 MEASURED_TRAFFIC = {
     ("a3b_8k", "combine_fwd", True): 270.1e6 + 33.6e6,
-    ("a3b_8k", "ffn_dact", True): 1016.9e6 + 305.5e6,
-    ("a3b_8k", "ffn_down", True): 646.4e6 + 268.5e6,
-    ("a3b_8k", "ffn_dx", True): 1632.6e6 + 268.5e6,
-    ("a3b_8k", "ffn_gate_up", True): 1536.0e6 + 379.2e6,
-    ("a3b_8k", "wgrad_down", True): 389.3e6 + 403.0e6,
-    ("a3b_8k", "wgrad_gate_up", True): 737.0e6 + 805.5e6,
+    ("a3b_8k", "ffn_dact", True): 1015.1e6 + 305.6e6,
+    ("a3b_8k", "ffn_down", True): 646.3e6 + 268.5e6,
+    ("a3b_8k", "ffn_dx", True): 1630.0e6 + 268.5e6,
+    ("a3b_8k", "ffn_gate_up", True): 1534.8e6 + 379.3e6,
+    ("a3b_8k", "wgrad_down", True): 389.8e6 + 403.1e6,
+    ("a3b_8k", "wgrad_gate_up", True): 739.8e6 + 805.6e6,
     ("a3b_8k", "combine_bwd", False): 314.9e6 + 268.7e6,
     ("a3b_8k", "combine_fwd", False): 270.1e6 + 33.6e6,
     ("a3b_8k", "ffn_dact", False): 1082.5e6 + 201.3e6,

@@ -254,7 +254,9 @@ template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma 
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const bool in_range = slab * BK + kidx(i) < K;
-      const char* g = in_range ? base[i] + slab * step + lane_off(i) : zeros;
+      uint32_t off = lane_off(i);
+      asm volatile("" : "+v"(off));                          // the 64-bit per-lane address is formed here, not kept in registers across the slab loop
+      const char* g = in_range ? base[i] + slab * step + off : zeros;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                        (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
     }

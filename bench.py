@@ -33,21 +33,21 @@ PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (
 # (fetch x 2.000, write x 1.000).  Keyed by (workload, kernel, rows gathered inside the products); absent = not measured.
 MEASURED_TRAFFIC = {
     ("a3b_8k", "combine_fwd", True): 270.1e6 + 33.6e6,
-    ("a3b_8k", "ffn_dact", True): 1015.1e6 + 305.6e6,
-    ("a3b_8k", "ffn_down", True): 646.3e6 + 268.5e6,
-    ("a3b_8k", "ffn_dx", True): 1630.0e6 + 268.5e6,
-    ("a3b_8k", "ffn_gate_up", True): 1534.8e6 + 379.3e6,
-    ("a3b_8k", "wgrad_down", True): 389.8e6 + 403.1e6,
-    ("a3b_8k", "wgrad_gate_up", True): 739.8e6 + 805.6e6,
-    ("a3b_8k", "combine_bwd", False): 314.9e6 + 268.7e6,
+    ("a3b_8k", "ffn_dact", True): 1017.6e6 + 305.6e6,
+    ("a3b_8k", "ffn_down", True): 647.5e6 + 268.5e6,
+    ("a3b_8k", "ffn_dx", True): 1634.0e6 + 268.5e6,
+    ("a3b_8k", "ffn_gate_up", True): 1516.1e6 + 386.6e6,
+    ("a3b_8k", "wgrad_down", True): 386.7e6 + 416.1e6,
+    ("a3b_8k", "wgrad_gate_up", True): 754.6e6 + 805.7e6,
+    ("a3b_8k", "combine_bwd", False): 315.0e6 + 268.7e6,
     ("a3b_8k", "combine_fwd", False): 270.1e6 + 33.6e6,
-    ("a3b_8k", "ffn_dact", False): 1082.5e6 + 201.3e6,
-    ("a3b_8k", "ffn_down", False): 647.1e6 + 268.5e6,
-    ("a3b_8k", "ffn_dx", False): 1629.2e6 + 268.5e6,
-    ("a3b_8k", "ffn_gate_up", False): 1585.3e6 + 380.3e6,
+    ("a3b_8k", "ffn_dact", False): 1084.8e6 + 201.3e6,
+    ("a3b_8k", "ffn_down", False): 647.0e6 + 268.5e6,
+    ("a3b_8k", "ffn_dx", False): 1627.6e6 + 268.5e6,
+    ("a3b_8k", "ffn_gate_up", False): 1551.0e6 + 379.6e6,
     ("a3b_8k", "permute_gather", False): 35.2e6 + 270.1e6,
-    ("a3b_8k", "wgrad_down", False): 404.0e6 + 403.4e6,
-    ("a3b_8k", "wgrad_gate_up", False): 726.4e6 + 805.5e6,
+    ("a3b_8k", "wgrad_down", False): 397.1e6 + 403.5e6,
+    ("a3b_8k", "wgrad_gate_up", False): 713.2e6 + 805.6e6,
 }
 
 

@@ -27,8 +27,14 @@
  *     counts, offsets and maps are int32.  P = T * k routed rows must fit in int32.
  *   - Weight layout: w_gate, w_up : [E, f, d];  w_down : [E, d, f]  (expert-major,
  *     out-features x in-features); gradients use the layout and dtype of their weight.
- *   - Every entry point validates its arguments on the host first; when it returns a
- *     non-zero status nothing has been launched.  moe_last_error() gives the reason.
+ *   - Every entry point validates its arguments on the host first; when it returns
+ *     MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED or MOE_ERR_WORKSPACE nothing has been launched.
+ *     MOE_ERR_HIP means a kernel launch itself was refused: the kernels of the call enqueued
+ *     before it still run, none after it is launched, and the outputs are undefined.  An entry
+ *     point clears the HIP runtime's last-error state of the calling thread when it starts to
+ *     launch, so an error left behind by an unrelated earlier call is not reported here.
+ *     moe_last_error() gives the reason.
+ *   - Workspaces must be 16-byte aligned.
  *   - Limits: 1 <= k <= 64, k <= E <= 1024; d and f multiples of 8; sizes > 0 except
  *     that T (or P) may be 0, which is a no-op.
  */
@@ -133,6 +139,11 @@ int32_t moe_grouped_gemm_swiglu_fwd(const void* xp, const void* w_gate, const vo
  * All three weight gradients are overwritten (not accumulated); experts without rows get
  * zeros.  g_save / u_save may both be NULL: G and U are then recomputed from xp (act is
  * still required).  `have_saved` in the workspace query says which variant will be called.
+ * The backward workspace holds [dG | dU] (2 P f elements), the recomputed G and U when nothing was
+ * saved, the device-built schedules, and room for fp32 partial weight-gradient tiles of experts
+ * whose rows are cut into several reduction chunks under skewed routing: at most 2 ceil(P / C)
+ * slots of 2 f d floats with C = max(2048, ceil(P / 32) rounded up to 256) rows (64 slots at most;
+ * with balanced routing none is touched).
  */
 size_t moe_grouped_gemm_swiglu_bwd_workspace_bytes(int dtype, int P, int d, int f, int E, int have_saved);
 int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, const void* g_save,
@@ -217,25 +228,22 @@ int32_t moe_router_bwd(const float* dlogits, const void* x, const void* w_router
                        void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * Per-kernel timing for measurement harnesses (not part of the layer's arithmetic).
- * moe_profile_enable(1): from now on every kernel the library launches is bracketed by a
- * pair of HIP events recorded on the launch stream (the library creates the events it
- * needs; this is the only place it allocates anything); records made so far are dropped.
- * moe_profile_enable(0) pauses the recording and keeps the records; moe_profile_enable(2)
- * resumes it without dropping anything (so a harness can sample some of its steps).
- * moe_profile_report: waits for the recorded events, writes one line per kernel
- * "name launches total_milliseconds\n" into buf ([host], cap bytes, NUL-terminated,
- * truncated if too small), clears the records and returns the size needed.
- * moe_profile_shader_clock: while profiling is on, the middle workgroup of each grouped-GEMM launch
- * (bf16 element type) measures the shader clock it ran at (shader-clock ticks against the fixed
- * 100 MHz reference counter, start to end of that workgroup).  Writes the latest value in MHz for
- * kernel i = 0..5 (gate/up, down, dA, dXp, dW_down, dW_gate/up) to mhz[i] ([host], n entries;
- * 0.0 where nothing was recorded or i >= 6).  Call it after the launch stream has been
- * synchronised; it copies 96 bytes from the device.
+ * Launch hook for measurement and tracing harnesses (not part of the layer's arithmetic; the
+ * hot path of Sec. 3.2.3 / 3.2.5 is what it observes).  When a hook is installed the library calls
+ *     hook(name, 0, stream, user)   just before it enqueues kernel `name` on `stream`,
+ *     hook(name, 1, stream, user)   just after,
+ *     hook(name, 2, stream, user)   when entry point `name` ("moe_permute", ...) is about to enqueue
+ *                                   its first kernel, and
+ *     hook(name, 3, stream, user)   after it has enqueued its last,
+ * on the calling thread of the entry point, so a harness can record its own events on that
+ * stream around each kernel and around each entry point.  name is a [host] static string
+ * ("ffn_gate_up", "combine_fwd", ...); stream is the hipStream_t the entry point was given.  The library itself creates no
+ * events, allocates nothing and copies nothing for this.  hook == NULL removes the hook.
+ * The hook must not call back into the library.  Installing or removing it while another
+ * thread is inside an entry point is safe; that call may or may not see the new hook.
  */
-int32_t moe_profile_enable(int on);
-size_t moe_profile_report(char* buf, size_t cap);
-int32_t moe_profile_shader_clock(double* mhz, int n);
+typedef void (*moe_launch_hook_t)(const char* name, int phase, void* stream, void* user);
+int32_t moe_set_launch_hook(moe_launch_hook_t hook, void* user);
 
 #ifdef __cplusplus
 }

@@ -3,10 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
-#include <map>
-#include <mutex>
-#include <string>
-#include <vector>
+#include <atomic>
 #include "moe_common.h"
 
 namespace moe {
@@ -21,46 +18,47 @@ int32_t fail(int32_t code, const char* fmt, ...) {
   return code;
 }
 
-int32_t check_launch(const char* what) {
-  hipError_t err = hipGetLastError();
-  if (err == hipSuccess) return MOE_OK;
-  return fail(MOE_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
-}
-
-// ---- per-kernel event timing -------------------------------------------------------------------
+// ---- launch bookkeeping ---------------------------------------------------------------------------
 namespace {
-struct ProfRecord { const char* name; hipEvent_t start, stop; };
-std::mutex g_prof_mutex;
-bool g_prof_on = false;
-unsigned long long* g_prof_clock = nullptr;   // device, kClockSlots x {shader ticks, 100 MHz ticks}
-std::vector<ProfRecord> g_prof_records;     // records in use
-std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;   // events ready for reuse
+thread_local hipError_t g_call_error = hipSuccess;    // first failed launch of the entry point running on this thread
+thread_local char g_call_where[64] = "";
+thread_local const char* g_call_entry = "";
+thread_local hipStream_t g_call_stream = nullptr;
+std::atomic<moe_launch_hook_t> g_hook{nullptr};
+std::atomic<void*> g_hook_user{nullptr};
 }  // namespace
 
-ProfScope::ProfScope(const char* name, hipStream_t stream) : stream_(stream), slot_(-1) {
-  if (!g_prof_on) return;
-  std::lock_guard<std::mutex> lock(g_prof_mutex);
-  ProfRecord r{name, nullptr, nullptr};
-  if (!g_prof_pool.empty()) {
-    r.start = g_prof_pool.back().first;
-    r.stop = g_prof_pool.back().second;
-    g_prof_pool.pop_back();
-  } else if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
-    return;
-  }
-  (void)hipEventRecord(r.start, stream);
-  g_prof_records.push_back(r);
-  slot_ = static_cast<int>(g_prof_records.size()) - 1;
+void begin_call(const char* entry, hipStream_t stream) {
+  (void)hipGetLastError();                             // an error left by an unrelated earlier call is not this call's
+  g_call_error = hipSuccess;
+  g_call_where[0] = 0;
+  g_call_entry = entry;
+  g_call_stream = stream;
+  if (moe_launch_hook_t h = g_hook.load(std::memory_order_acquire)) h(entry, 2, stream, g_hook_user.load(std::memory_order_acquire));
 }
 
-ProfScope::~ProfScope() {
-  if (slot_ < 0) return;
-  std::lock_guard<std::mutex> lock(g_prof_mutex);
-  (void)hipEventRecord(g_prof_records[slot_].stop, stream_);
+void note_hip_failure(const char* what, hipError_t err) {
+  if (err == hipSuccess || g_call_error != hipSuccess) return;
+  g_call_error = err;
+  snprintf(g_call_where, sizeof(g_call_where), "%s", what);
 }
 
-unsigned long long* prof_clock_slot(int which) {
-  return (g_prof_on && g_prof_clock && which >= 0 && which < kClockSlots) ? g_prof_clock + 2 * which : nullptr;
+bool launch_begin(const char* name, hipStream_t stream) {
+  if (g_call_error != hipSuccess) return false;
+  if (moe_launch_hook_t h = g_hook.load(std::memory_order_acquire)) h(name, 0, stream, g_hook_user.load(std::memory_order_acquire));
+  return true;
+}
+
+void launch_end(const char* name, hipStream_t stream) {
+  note_hip_failure(name, hipGetLastError());
+  if (moe_launch_hook_t h = g_hook.load(std::memory_order_acquire)) h(name, 1, stream, g_hook_user.load(std::memory_order_acquire));
+}
+
+int32_t end_call() {
+  if (moe_launch_hook_t h = g_hook.load(std::memory_order_acquire)) h(g_call_entry, 3, g_call_stream, g_hook_user.load(std::memory_order_acquire));
+  if (g_call_error == hipSuccess) return MOE_OK;
+  return fail(MOE_ERR_HIP, "%s: launch of %s failed: %s (kernels enqueued before it still run; none after it was launched)", g_call_entry,
+              g_call_where, hipGetErrorString(g_call_error));
 }
 
 static int32_t check_ffn_dims(const char* who, int dtype, int P, int d, int f, int E) {
@@ -79,64 +77,11 @@ using namespace moe;
 extern "C" const char* moe_version(void) { return "0.1.0"; }
 extern "C" const char* moe_last_error(void) { return g_error; }
 
-extern "C" int32_t moe_profile_enable(int on) {
-  std::lock_guard<std::mutex> lock(g_prof_mutex);
-  if (on && !g_prof_clock) {
-    if (hipMalloc(reinterpret_cast<void**>(&g_prof_clock), kClockSlots * 2 * sizeof(unsigned long long)) != hipSuccess) {
-      g_prof_clock = nullptr;
-      return fail(MOE_ERR_HIP, "moe_profile_enable: cannot allocate the clock slots");
-    }
-  }
-  if (on == 1) {                                       // a fresh start: drop what was recorded so far
-    if (hipMemset(g_prof_clock, 0, kClockSlots * 2 * sizeof(unsigned long long)) != hipSuccess)
-      return fail(MOE_ERR_HIP, "moe_profile_enable: cannot clear the clock slots");
-    for (auto& r : g_prof_records) g_prof_pool.emplace_back(r.start, r.stop);
-    g_prof_records.clear();
-  }
-  g_prof_on = on != 0;                                 // 0: pause (records stay), 2: resume
+extern "C" int32_t moe_set_launch_hook(moe_launch_hook_t hook, void* user) {
+  g_hook.store(nullptr, std::memory_order_release);    // never pair the new user pointer with the old function
+  g_hook_user.store(user, std::memory_order_release);
+  g_hook.store(hook, std::memory_order_release);
   return MOE_OK;
-}
-
-extern "C" int32_t moe_profile_shader_clock(double* mhz, int n) {
-  MOE_REQUIRE(mhz != nullptr && n >= 0, MOE_ERR_INVALID_ARG, "moe_profile_shader_clock: null output or negative count");
-  unsigned long long host[kClockSlots * 2] = {};
-  {
-    std::lock_guard<std::mutex> lock(g_prof_mutex);
-    if (g_prof_clock && hipMemcpy(host, g_prof_clock, sizeof(host), hipMemcpyDeviceToHost) != hipSuccess)
-      return fail(MOE_ERR_HIP, "moe_profile_shader_clock: copy from the device failed");
-  }
-  for (int i = 0; i < n; ++i)
-    mhz[i] = (i < kClockSlots && host[2 * i + 1] > 0) ? 100.0 * static_cast<double>(host[2 * i]) / static_cast<double>(host[2 * i + 1]) : 0.0;
-  return MOE_OK;
-}
-
-extern "C" size_t moe_profile_report(char* buf, size_t cap) {
-  std::lock_guard<std::mutex> lock(g_prof_mutex);
-  struct Agg { long count = 0; double ms = 0.0; };
-  std::map<std::string, Agg> agg;
-  std::vector<std::string> order;
-  for (auto& r : g_prof_records) {
-    float ms = 0.0f;
-    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
-    if (!agg.count(r.name)) order.push_back(r.name);
-    Agg& a = agg[r.name];
-    a.count += 1;
-    a.ms += ms;
-  }
-  for (auto& r : g_prof_records) g_prof_pool.emplace_back(r.start, r.stop);
-  g_prof_records.clear();
-  std::string out;
-  char line[256];
-  for (auto& name : order) {
-    snprintf(line, sizeof(line), "%s %ld %.6f\n", name.c_str(), agg[name].count, agg[name].ms);
-    out += line;
-  }
-  if (buf && cap > 0) {
-    size_t n = out.size() < cap - 1 ? out.size() : cap - 1;
-    memcpy(buf, out.data(), n);
-    buf[n] = 0;
-  }
-  return out.size() + 1;
 }
 
 extern "C" size_t moe_grouped_gemm_swiglu_fwd_workspace_bytes(int dtype, int P, int d, int f, int E) {
@@ -162,8 +107,9 @@ extern "C" int32_t moe_grouped_gemm_swiglu_fwd(const void* xp, const void* w_gat
   const size_t need = moe_grouped_gemm_swiglu_fwd_workspace_bytes(dtype, P, d, f, E);
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_fwd: workspace null, misaligned or smaller than %zu bytes", need);
   FfnFwdArgs a{xp, w_gate, w_up, w_down, P, d, f, E, offsets, g_save, u_save, act, yp, ws, static_cast<hipStream_t>(stream)};
+  begin_call("moe_grouped_gemm_swiglu_fwd", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) ffn_fwd_bf16(a); else ffn_fwd_f32(a);
-  return check_launch("moe_grouped_gemm_swiglu_fwd");
+  return end_call();
 }
 
 extern "C" int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, const void* g_save,
@@ -182,8 +128,9 @@ extern "C" int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, 
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_bwd: workspace null, misaligned or smaller than %zu bytes", need);
   FfnBwdArgs a{dyp, xp, g_save, u_save, act, w_gate, w_up, w_down, P, d, f, E, offsets, dxp, dw_gate, dw_up, dw_down, ws,
                static_cast<hipStream_t>(stream)};
+  begin_call("moe_grouped_gemm_swiglu_bwd", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) ffn_bwd_bf16(a); else ffn_bwd_f32(a);
-  return check_launch("moe_grouped_gemm_swiglu_bwd");
+  return end_call();
 }
 
 // ---- grouped FFN reading its rows by token (no expert-ordered copies) -------------------------------------
@@ -220,8 +167,9 @@ extern "C" int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int 
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_fwd_gather: workspace null, misaligned or smaller than %zu bytes", need);
   FfnFwdGatherArgs a{x, T, k, pair_of_row, w_gate, w_up, w_down, P, d, f, E, offsets, g_save, u_save, act, yp, ws,
                      static_cast<hipStream_t>(stream)};
+  begin_call("moe_grouped_gemm_swiglu_fwd_gather", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) ffn_fwd_gather_bf16(a); else ffn_fwd_gather_f32(a);
-  return check_launch("moe_grouped_gemm_swiglu_fwd_gather");
+  return end_call();
 }
 
 extern "C" int32_t moe_grouped_gemm_swiglu_bwd_gather(const void* dy, const void* x, int T, int k, const float* topk_w,
@@ -243,8 +191,9 @@ extern "C" int32_t moe_grouped_gemm_swiglu_bwd_gather(const void* dy, const void
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_bwd_gather: workspace null, misaligned or smaller than %zu bytes", need);
   FfnBwdGatherArgs a{dy, x, T, k, topk_w, pair_of_row, g_save, u_save, w_gate, w_up, w_down, P, d, f, E, offsets, dxp, dw_gate,
                      dw_up, dw_down, dtopk_w, ws, static_cast<hipStream_t>(stream)};
+  begin_call("moe_grouped_gemm_swiglu_bwd_gather", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) ffn_bwd_gather_bf16(a); else ffn_bwd_gather_f32(a);
-  return check_launch("moe_grouped_gemm_swiglu_bwd_gather");
+  return end_call();
 }
 
 // ---- router linear -----------------------------------------------------------------------------------
@@ -280,8 +229,9 @@ extern "C" int32_t moe_router_logits(const void* x, const void* w_router, int dt
   const size_t need = moe_router_logits_workspace_bytes(dtype, T, d, E);
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "router_logits: workspace null, misaligned or smaller than %zu bytes", need);
   RouterFwdArgs a{x, w_router, T, d, E, logits, ws, static_cast<hipStream_t>(stream)};
+  begin_call("moe_router_logits", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) router_fwd_bf16(a); else router_fwd_f32(a);
-  return check_launch("moe_router_logits");
+  return end_call();
 }
 
 extern "C" int32_t moe_router_bwd(const float* dlogits, const void* x, const void* w_router, int dtype, int T, int d, int E,
@@ -295,12 +245,14 @@ extern "C" int32_t moe_router_bwd(const float* dlogits, const void* x, const voi
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "router_bwd: workspace null, misaligned or smaller than %zu bytes", need);
   if (T == 0) {   // no rows: the weight gradient is all zeros (a fill kernel, not a memset node: callers may capture this)
     const size_t words = static_cast<size_t>(E) * d * elem_size(dtype) / 4;
-    hipLaunchKernelGGL(zero_words_kernel, dim3(static_cast<unsigned>((words + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<uint32_t*>(dw_router), words);
-    return check_launch("moe_router_bwd");
+    begin_call("moe_router_bwd", static_cast<hipStream_t>(stream));
+    MOE_LAUNCH("zero_dw_router", zero_words_kernel, dim3(static_cast<unsigned>((words + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+               static_cast<uint32_t*>(dw_router), words);
+    return end_call();
   }
   RouterBwdArgs a{dlogits, x, w_router, T, d, E, accumulate != 0, dx, dw_router, ws, static_cast<hipStream_t>(stream)};
+  begin_call("moe_router_bwd", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) router_bwd_bf16(a); else router_bwd_f32(a);
-  return check_launch("moe_router_bwd");
+  return end_call();
 }
 

@@ -30,7 +30,7 @@
 // The router linear (logits, its weight gradient, its part of the input gradient) runs on
 // the same skeleton with a single segment of all rows.
 #include <algorithm>
-#include <cstdlib>
+#include <mutex>
 #include <type_traits>
 #include "moe_common.h"
 
@@ -675,7 +675,6 @@ struct RowArgs {
   const bf16_t* g;         // kDAct: saved pre-activations
   const bf16_t* u;
   const bf16_t* zeros;     // at least 16 zero bytes (source of out-of-range reduction indices)
-  unsigned long long* clock;   // null, or where the middle workgroup records the clock it ran at
   // FUSED kernels: `a` is the token-major matrix [T, lda] and row r of the product reads a[row_token[r]]
   const int32_t* row_token;    // [P (+ padding)]
   const float* row_w;          // kDAct: combine weight of each row; the product's rows are scaled by it
@@ -697,7 +696,6 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   const int n_row_tiles = p.rt.count[0];
   const int v = xcd_remap(blockIdx.x, n_row_tiles * p.n_tiles_n);
   if (v < 0) return;
-  ClockStamp stamp(p.clock);
   const int mt = v / p.n_tiles_n, nt = v % p.n_tiles_n;
   const int e = p.rt.expert[mt];
   const int row0 = p.rt.row0[mt];
@@ -1064,7 +1062,6 @@ struct WgradArgs {
   bf16_t* out0; bf16_t* out1; int m_split;     // out1 rows are (m - m_split)
   float* partial;                              // [max_slots][M][N]
   const bf16_t* zeros;     // at least 16 zero bytes
-  unsigned long long* clock;   // null, or where the middle workgroup records the clock it ran at
   const int32_t* row_token;    // GATHER kernels: [P + padding], token of each expert-ordered row
 };
 
@@ -1102,7 +1099,6 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   const int per_u = per_e / g;                          // g divides slow, so it divides per_e
   const int unit = (blockIdx.x / kXcds) / per_u * kXcds + blockIdx.x % kXcds;
   if (unit >= n_items * g) return;
-  ClockStamp stamp(p.clock);
   const int item = unit / g;
   const int vi = (unit % g) * per_u + (blockIdx.x / kXcds) % per_u;   // position among the item's tiles
   const int mt = MT_FASTEST ? vi % p.tiles_m : vi / spans_n;
@@ -1239,32 +1235,18 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
 // Host side
 // ============================================================================================
 // Tile shapes in use.
-//   TileBig (default): 256 x 256 outputs, 64-wide slabs, one 8-wave workgroup per CU (2 x 4 wavefronts of
-//     128 x 64), two stages of 64 KiB.  A slab row is a whole 128-byte line, so the tile needs a third of the
-//     L2 requests per flop of TileRow and two thirds of the bytes; measured inside the layer step it is
-//     3 % faster over the six products of the 30B-class shapes (6 % on the down product, 3.6 % slower on dA).
-//   TileRow (MOE_GEMM_TILE=0 in the environment): 128 x 256, 32-wide slabs, two 4-wave workgroups per CU
-//     (2 x 2 wavefronts of 64 x 128), three stages of 24 KiB each.
-//   TileRouter: 64 x 128 x 64 for the skinny products with N = E, two workgroups per CU.
+//   TileBig: 256 x 256 outputs, 64-wide slabs, one 8-wave workgroup per CU (2 x 4 wavefronts of 128 x 64), two
+//     stages of 64 KiB.  A slab row is a whole 128-byte line: the fewest L2 requests per flop that fit the CU.
 //   TileBigW16: the TileBig ring under 16 waves (4 x 4 of 64 x 64, four per SIMD, 128 VGPRs) for the weight
 //     gradients: both their operands are read transposed (twice the LDS read instructions per MFMA), and four
 //     waves per SIMD cover that better -- 3-5 % faster on dW_down at every size and on [dW_gate; dW_up] from
 //     about 1000 rows per expert; the row products are 2-5 % slower with it and keep 8 waves.
+//   TileRouter: 64 x 128 x 64 for the skinny products with N = E, two workgroups per CU.
 typedef Tile<256, 256, 64, 2, 4, 2> TileBig;
 typedef Tile<256, 256, 64, 4, 4, 2> TileBigW16;
-typedef Tile<128, 256, 32, 2, 2, 3> TileRow;
 typedef Tile<64, 128, 64, 2, 2, 3> TileRouter;
 
-static int tile_choice() {
-  static int choice = -1;
-  if (choice < 0) {
-    const char* s = getenv("MOE_GEMM_TILE");
-    choice = (s && atoi(s) == 0) ? 0 : 1;
-  }
-  return choice;
-}
-
-static int row_bm() { return tile_choice() == 1 ? TileBig::BM : TileRow::BM; }
+static int row_bm() { return TileBig::BM; }
 // bound used for workspace sizing: the smallest row tile gives the longest list
 static int max_row_tiles(int P, int E) { return ceil_div(P, 128) + E; }
 
@@ -1347,38 +1329,44 @@ static WgradItems wgrad_items_at(void* ws, const WsLayout& w, int P, int E) {
   return it;
 }
 
+// A kernel that needs more than 64 KiB of dynamic LDS has to be granted it once per device.  Each kernel has its
+// own set of flags (a static of its launcher's template instance); the status is kept, and a failure is reported
+// through the call's launch status instead of surfacing later as an opaque launch error.
+constexpr int kMaxDevices = 64;
+struct LdsGrant { std::once_flag once[kMaxDevices]; hipError_t status[kMaxDevices] = {}; };
+static bool allow_lds(LdsGrant& g, const void* kernel, int bytes, const char* name) {
+  int dev = 0;
+  hipError_t err = hipGetDevice(&dev);
+  if (err == hipSuccess && (dev < 0 || dev >= kMaxDevices)) err = hipErrorInvalidDevice;
+  if (err == hipSuccess) {
+    std::call_once(g.once[dev], [&] { g.status[dev] = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+    err = g.status[dev];
+  }
+  if (err != hipSuccess) note_hip_failure(name, err);
+  return err == hipSuccess;
+}
+
 static unsigned padded_grid(int tiles) { return static_cast<unsigned>(ceil_div(tiles < 1 ? 1 : tiles, kXcds) * kXcds); }
 
 template <int KIND, class T, bool FUSED = false>
 static void launch_row_t(RowArgs p, int P, int E, hipStream_t s) {
   static const char* const names[6] = {"ffn_gate_up", "ffn_down", "ffn_dact", "ffn_dx", "router_logits", "router_dx"};
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&row_grouped_kernel<KIND, T, FUSED>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsAlloc);
-    attr_set = true;
-  }
+  static LdsGrant grant;
+  if (!allow_lds(grant, reinterpret_cast<const void*>(&row_grouped_kernel<KIND, T, FUSED>), T::kLdsAlloc, names[KIND])) return;
   p.n_tiles_n = ceil_div(p.N, KIND == kGateUp ? T::BN / 2 : T::BN);
-  p.clock = KIND < 4 ? prof_clock_slot(KIND) : nullptr;
   const unsigned grid = padded_grid((ceil_div(P, T::BM) + E) * p.n_tiles_n);
   MOE_LAUNCH(names[KIND], (row_grouped_kernel<KIND, T, FUSED>), dim3(grid), dim3(T::kThreads), T::kLdsAlloc, s, p);
 }
 
 template <int KIND, bool FUSED = false>
 static void launch_row(const RowArgs& p, int P, int E, hipStream_t s) {
-  if (tile_choice() == 1) launch_row_t<KIND, TileBig, FUSED>(p, P, E, s);
-  else launch_row_t<KIND, TileRow, FUSED>(p, P, E, s);
+  launch_row_t<KIND, TileBig, FUSED>(p, P, E, s);
 }
 
 template <int WHICH, class T, bool GATHER = false>
 static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<WHICH, T, GATHER>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsAlloc);
-    attr_set = true;
-  }
-  p.clock = WHICH < 2 ? prof_clock_slot(4 + WHICH) : nullptr;
+  static LdsGrant grant;
+  if (!allow_lds(grant, reinterpret_cast<const void*>(&wgrad_kernel<WHICH, T, GATHER>), T::kLdsAlloc, "wgrad")) return;
   p.tiles_m = ceil_div(p.M, T::BM);
   p.tiles_n = ceil_div(p.N, T::BN);
   // units are dealt to the XCDs in groups of 8, the last group may be partial: up to 8 more units than items
@@ -1393,15 +1381,11 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
 
 template <int WHICH, bool GATHER = false>
 static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
-  if (tile_choice() == 1) {
-    // [dW_gate; dW_up] with short reductions is faster with TileBig's paired column tiles
-    if (WHICH == 0 || (WHICH == 1 && p.P >= 1024L * p.E)) {
-      if constexpr (WHICH < 2) launch_wgrad_t<WHICH, TileBigW16, GATHER>(p, s);
-    } else {
-      launch_wgrad_t<WHICH, TileBig, GATHER>(p, s);
-    }
+  // [dW_gate; dW_up] with short reductions is faster with TileBig's paired column tiles
+  if (WHICH == 0 || (WHICH == 1 && p.P >= 1024L * p.E)) {
+    if constexpr (WHICH < 2) launch_wgrad_t<WHICH, TileBigW16, GATHER>(p, s);
   } else {
-    launch_wgrad_t<WHICH, TileRow, GATHER>(p, s);
+    launch_wgrad_t<WHICH, TileBig, GATHER>(p, s);
   }
 }
 
@@ -1520,7 +1504,7 @@ __global__ __launch_bounds__(256) void finish_dw_kernel(const float* __restrict_
 }
 
 // column slots of the partial dot products: one per (column tile, wavefront column) of the dA product
-static int dw_slots(int f) { return tile_choice() == 1 ? ceil_div(f, TileBig::BN) * TileBig::WGN : ceil_div(f, TileRow::BN) * TileRow::WGN; }
+static int dw_slots(int f) { return ceil_div(f, TileBig::BN) * TileBig::WGN; }
 
 struct GatherWs { size_t row_token, row_w, act_w, dw_partial, total; };
 static GatherWs gather_ws(const WsLayout& w, int P, int f, bool bwd) {

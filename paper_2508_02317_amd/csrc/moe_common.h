@@ -9,42 +9,29 @@ namespace moe {
 
 // ---- host-side error reporting ---------------------------------------------------------
 int32_t fail(int32_t code, const char* fmt, ...);   // records the message, returns code
-int32_t check_launch(const char* what);              // hipGetLastError -> MOE_ERR_HIP
 
 #define MOE_REQUIRE(cond, code, ...) \
   do { if (!(cond)) return ::moe::fail((code), __VA_ARGS__); } while (0)
 
-// ---- optional per-kernel timing (HIP events on the launch stream) ----------------------------
-// Off by default; when moe_profile_enable(1) has been called every kernel launch is bracketed
-// by a pair of events recorded on the same stream, read back by moe_profile_report().
-struct ProfScope {
-  ProfScope(const char* name, hipStream_t stream);
-  ~ProfScope();
-  hipStream_t stream_;
-  int slot_;
-};
+// ---- launching ------------------------------------------------------------------------------
+// Every kernel goes through MOE_LAUNCH.  An entry point calls begin_call() once its arguments are
+// validated: that forgets whatever error an earlier, unrelated HIP call left behind on this thread.
+// The status of each launch is then read straight after it; after the first failure the remaining
+// launches of the call are skipped, and end_call() reports the kernel that failed.
+// A harness may install a hook (moe_set_launch_hook) that is told about every launch, before and
+// after it is enqueued, with the stream it goes to -- that is all the library offers for timing.
+void begin_call(const char* entry, hipStream_t stream);
+int32_t end_call();                                  // MOE_ERR_HIP if a launch of this call failed
+bool launch_begin(const char* name, hipStream_t stream);   // false: an earlier launch of this call failed
+void launch_end(const char* name, hipStream_t stream);
+void note_hip_failure(const char* what, hipError_t err);   // first failure of the call wins
 #define MOE_LAUNCH(name, kern, grid, block, shmem, stream, ...)            \
   do {                                                                     \
-    ::moe::ProfScope moe_prof_scope_(name, stream);                        \
-    hipLaunchKernelGGL(kern, grid, block, shmem, stream, __VA_ARGS__);     \
+    if (::moe::launch_begin(name, stream)) {                               \
+      hipLaunchKernelGGL(kern, grid, block, shmem, stream, __VA_ARGS__);   \
+      ::moe::launch_end(name, stream);                                     \
+    }                                                                      \
   } while (0)
-
-// While profiling is on, the workgroup in the middle of the grid of each grouped-GEMM launch records how
-// many shader-clock ticks and how many ticks of the fixed 100 MHz reference passed between its start and
-// its end: the clock these kernels actually ran at (the first workgroups of a launch still see the higher
-// clock left by whatever ran before).  Returns the two-word device slot of GEMM kernel `which` (0..5), or null.
-constexpr int kClockSlots = 6;
-unsigned long long* prof_clock_slot(int which);
-struct ClockStamp {
-  unsigned long long* out_;
-  unsigned long long ref0_, clk0_;
-  __device__ __forceinline__ explicit ClockStamp(unsigned long long* out) : out_(blockIdx.x == gridDim.x / 2 ? out : nullptr), ref0_(0), clk0_(0) {
-    if (out_) { ref0_ = wall_clock64(); clk0_ = clock64(); }
-  }
-  __device__ __forceinline__ ~ClockStamp() {
-    if (out_ && threadIdx.x == 0) { out_[0] = clock64() - clk0_; out_[1] = wall_clock64() - ref0_; }
-  }
-};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

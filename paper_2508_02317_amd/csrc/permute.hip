@@ -278,8 +278,9 @@ extern "C" int32_t moe_permute(const void* x, int dtype, int T, int d, int E, in
   MOE_REQUIRE(aligned16(x) && aligned16(xp), MOE_ERR_INVALID_ARG, "permute: x / xp must be 16-byte aligned");
   size_t hist_off = 0;
   const size_t need = permute_ws_layout(T, E, k, &hist_off);
-  MOE_REQUIRE(ws && ws_bytes >= need, MOE_ERR_WORKSPACE, "permute: workspace null or smaller than %zu bytes", need);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "permute: workspace null, misaligned or smaller than %zu bytes", need);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_permute", s);
   const int P = T * k;
   const int nchunks = ceil_div(P, kChunkPairs);
   int32_t* rank = static_cast<int32_t*>(ws);
@@ -290,7 +291,7 @@ extern "C" int32_t moe_permute(const void* x, int dtype, int T, int d, int E, in
   MOE_LAUNCH(x ? "permute_gather" : "permute_maps", permute_gather_kernel, dim3(ceil_div(T, kMoverThreads / 64)), dim3(kMoverThreads), 0, s,
                      static_cast<const uint4*>(x), T, k, E, n16, topk_idx, rank, hist, nchunks,
                      static_cast<uint4*>(xp), row_of_pair, pair_of_row);
-  return check_launch("moe_permute");
+  return end_call();
 }
 
 extern "C" int32_t moe_unpermute_combine_fwd(const void* yp, int dtype, int T, int d, int k,
@@ -301,6 +302,7 @@ extern "C" int32_t moe_unpermute_combine_fwd(const void* yp, int dtype, int T, i
   MOE_REQUIRE(yp && row_of_pair && y, MOE_ERR_INVALID_ARG, "combine_fwd: null pointer");
   MOE_REQUIRE(aligned16(yp) && aligned16(y), MOE_ERR_INVALID_ARG, "combine_fwd: yp / y must be 16-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_unpermute_combine_fwd", s);
   const int n16 = d * elem_size(dtype) / 16;
   const size_t total = static_cast<size_t>(T) * n16;
   const unsigned blocks = static_cast<unsigned>((total + kMoverThreads - 1) / kMoverThreads);
@@ -316,7 +318,7 @@ extern "C" int32_t moe_unpermute_combine_fwd(const void* yp, int dtype, int T, i
     else if (k == 2) MOE_COMBINE_FWD(MOE_F32, 2); else MOE_COMBINE_FWD(MOE_F32, 1);
   }
 #undef MOE_COMBINE_FWD
-  return check_launch("moe_unpermute_combine_fwd");
+  return end_call();
 }
 
 extern "C" int32_t moe_unpermute_combine_bwd(const void* dy, const void* yp, int dtype, int T, int d, int k,
@@ -327,6 +329,7 @@ extern "C" int32_t moe_unpermute_combine_bwd(const void* dy, const void* yp, int
   MOE_REQUIRE(dy && yp && topk_w && row_of_pair && dyp && dw, MOE_ERR_INVALID_ARG, "combine_bwd: null pointer");
   MOE_REQUIRE(aligned16(dy) && aligned16(yp) && aligned16(dyp), MOE_ERR_INVALID_ARG, "combine_bwd: dy / yp / dyp must be 16-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_unpermute_combine_bwd", s);
   const int n16 = d * elem_size(dtype) / 16;
   const unsigned blocks = static_cast<unsigned>(ceil_div(T, kMoverThreads / 64));
   if (dtype == MOE_BF16)
@@ -337,5 +340,5 @@ extern "C" int32_t moe_unpermute_combine_bwd(const void* dy, const void* yp, int
     MOE_LAUNCH("combine_bwd", combine_bwd_kernel<MOE_F32>, dim3(blocks), dim3(kMoverThreads), 0, s,
                        static_cast<const uint4*>(dy), static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair,
                        static_cast<uint4*>(dyp), dw);
-  return check_launch("moe_unpermute_combine_bwd");
+  return end_call();
 }

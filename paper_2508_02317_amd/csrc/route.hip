@@ -243,9 +243,10 @@ extern "C" int32_t moe_route_topk(const float* logits, int T, int E, int k, int 
   if (int32_t rc = check_route_dims(T, E, k)) return rc;
   MOE_REQUIRE(counts && offsets, MOE_ERR_INVALID_ARG, "route: counts/offsets must not be null");
   MOE_REQUIRE(T == 0 || (logits && topk_idx && topk_w), MOE_ERR_INVALID_ARG, "route: null logits/topk_idx/topk_w");
-  MOE_REQUIRE(ws && ws_bytes >= moe_route_topk_workspace_bytes(T, E, k), MOE_ERR_WORKSPACE,
-              "route: workspace null or smaller than %zu bytes", moe_route_topk_workspace_bytes(T, E, k));
+  MOE_REQUIRE(ws && ws_bytes >= moe_route_topk_workspace_bytes(T, E, k) && aligned16(ws), MOE_ERR_WORKSPACE,
+              "route: workspace null, misaligned or smaller than %zu bytes", moe_route_topk_workspace_bytes(T, E, k));
   hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_route_topk", s);
   const int nblk = route_blocks(T);
   int32_t* hist = static_cast<int32_t*>(ws);
   const int vpl = ceil_div(E, 64);
@@ -260,7 +261,7 @@ extern "C" int32_t moe_route_topk(const float* logits, int T, int E, int k, int 
   int epad = 64;
   while (epad < E) epad <<= 1;
   MOE_LAUNCH("route_scan", route_scan_kernel, dim3(1), dim3(1024), 0, s, hist, nblk, E, epad, counts, offsets);
-  return check_launch("moe_route_topk");
+  return end_call();
 }
 
 static int hist_blocks(int n_pairs) {
@@ -278,16 +279,17 @@ extern "C" int32_t moe_expert_offsets(const int32_t* topk_idx, int n_pairs, int 
   MOE_REQUIRE(n_pairs >= 0 && E > 0, MOE_ERR_INVALID_ARG, "expert_offsets: need n_pairs >= 0, E > 0");
   MOE_REQUIRE(E <= kMaxExperts, MOE_ERR_UNSUPPORTED, "expert_offsets: E=%d above the built maximum %d", E, kMaxExperts);
   MOE_REQUIRE(counts && offsets && (n_pairs == 0 || topk_idx), MOE_ERR_INVALID_ARG, "expert_offsets: null pointer");
-  MOE_REQUIRE(ws && ws_bytes >= moe_expert_offsets_workspace_bytes(n_pairs, E), MOE_ERR_WORKSPACE,
-              "expert_offsets: workspace null or smaller than %zu bytes", moe_expert_offsets_workspace_bytes(n_pairs, E));
+  MOE_REQUIRE(ws && ws_bytes >= moe_expert_offsets_workspace_bytes(n_pairs, E) && aligned16(ws), MOE_ERR_WORKSPACE,
+              "expert_offsets: workspace null, misaligned or smaller than %zu bytes", moe_expert_offsets_workspace_bytes(n_pairs, E));
   hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_expert_offsets", s);
   const int nblk = hist_blocks(n_pairs);
   int32_t* hist = static_cast<int32_t*>(ws);
   MOE_LAUNCH("pair_hist", pair_hist_kernel, dim3(nblk), dim3(kRouteThreads), 0, s, topk_idx, n_pairs, E, hist);
   int epad = 64;
   while (epad < E) epad <<= 1;
   MOE_LAUNCH("route_scan", route_scan_kernel, dim3(1), dim3(1024), 0, s, hist, nblk, E, epad, counts, offsets);
-  return check_launch("moe_expert_offsets");
+  return end_call();
 }
 
 extern "C" int32_t moe_route_topk_bwd(const float* dw, const float* topk_w, const int32_t* topk_idx,
@@ -298,6 +300,7 @@ extern "C" int32_t moe_route_topk_bwd(const float* dw, const float* topk_w, cons
   MOE_REQUIRE(dw && topk_w && topk_idx && dlogits, MOE_ERR_INVALID_ARG, "route_bwd: null pointer");
   MOE_REQUIRE(renorm || logits, MOE_ERR_INVALID_ARG, "route_bwd: logits required when renorm == 0");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_route_topk_bwd", s);
   const int nblk = route_blocks(T);
   const int vpl = ceil_div(E, 64);
 #define MOE_LAUNCH_RBWD(V) \
@@ -308,5 +311,5 @@ extern "C" int32_t moe_route_topk_bwd(const float* dw, const float* topk_w, cons
   else if (vpl <= 8) MOE_LAUNCH_RBWD(8);
   else MOE_LAUNCH_RBWD(16);
 #undef MOE_LAUNCH_RBWD
-  return check_launch("moe_route_topk_bwd");
+  return end_call();
 }

@@ -29,8 +29,12 @@ EXPORTS = [
     "moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes", "moe_grouped_gemm_swiglu_bwd_gather",
     "moe_unpermute_combine_fwd", "moe_unpermute_combine_bwd",
     "moe_router_logits_workspace_bytes", "moe_router_logits", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
-    "moe_profile_enable", "moe_profile_report", "moe_profile_shader_clock",
+    "moe_set_launch_hook",
 ]
+
+
+# void hook(const char* kernel_name, int phase, void* stream, void* user)
+LAUNCH_HOOK = ctypes.CFUNCTYPE(None, ctypes.c_char_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p)
 
 
 class MoEError(RuntimeError):
@@ -92,12 +96,8 @@ def _load():
     lib.moe_router_bwd_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.moe_router_bwd.restype = ctypes.c_int32
     lib.moe_router_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
-    lib.moe_profile_enable.restype = ctypes.c_int32
-    lib.moe_profile_enable.argtypes = [i32]
-    lib.moe_profile_shader_clock.restype = ctypes.c_int32
-    lib.moe_profile_shader_clock.argtypes = [ctypes.POINTER(ctypes.c_double), i32]
-    lib.moe_profile_report.restype = sz
-    lib.moe_profile_report.argtypes = [ctypes.c_char_p, sz]
+    lib.moe_set_launch_hook.restype = ctypes.c_int32
+    lib.moe_set_launch_hook.argtypes = [LAUNCH_HOOK, vp]
     return lib
 
 
@@ -112,28 +112,9 @@ def moe_last_error():
     return lib.moe_last_error().decode()
 
 
-def moe_profile_enable(on):
-    """1: start afresh, 0: pause (records are kept), 2: resume."""
-    _check(lib.moe_profile_enable(int(on)))
-
-
-def moe_profile_shader_clock():
-    """MHz the middle workgroup of each grouped-GEMM launch ran at (0.0 where nothing was recorded)."""
-    names = ("ffn_gate_up", "ffn_down", "ffn_dact", "ffn_dx", "wgrad_down", "wgrad_gate_up")
-    out = (ctypes.c_double * len(names))()
-    _check(lib.moe_profile_shader_clock(out, len(names)))
-    return {n: float(v) for n, v in zip(names, out)}
-
-
-def moe_profile_report():
-    """-> {kernel name: (launches, total milliseconds)} since the last report."""
-    buf = ctypes.create_string_buffer(1 << 16)
-    lib.moe_profile_report(buf, len(buf))
-    out = {}
-    for line in buf.value.decode().splitlines():
-        name, count, ms = line.split()
-        out[name] = (int(count), float(ms))
-    return out
+def moe_set_launch_hook(hook):
+    """hook: a LAUNCH_HOOK instance (kept alive by the caller) or None to remove it."""
+    _check(lib.moe_set_launch_hook(hook if hook is not None else LAUNCH_HOOK(), None))
 
 
 def _check(status):

@@ -83,6 +83,21 @@ int32_t moe_route_topk(const float* logits, int T, int E, int k, int renorm,
                        int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
                        void* ws, size_t ws_bytes, void* stream);
 
+/* moe_route_topk for callers that cannot allocate and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without ws), same
+ * kernels, same results bit for bit.  The per-workgroup histogram rows live in a static device array
+ * inside the library instead: moe_route_topk_noalloc_max_bytes() bytes (2 MiB) held by every GPU the
+ * library runs on until the process ends.  A shape whose moe_route_topk_workspace_bytes(T,E,k) exceeds
+ * that maximum is rejected with MOE_ERR_UNSUPPORTED and nothing is launched.  The call allocates and
+ * frees nothing (the first call on a device only looks up the array's address).  All calls on one GPU
+ * share the array: calls that may overlap on that GPU (different streams) race and must be ordered by
+ * the caller; calls on the same stream are ordered by the stream.
+ */
+size_t moe_route_topk_noalloc_max_bytes(void);
+int32_t moe_route_topk_noalloc(const float* logits, int T, int E, int k, int renorm,
+                               int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
+                               void* stream);
+
 /* Counts and offsets of an assignment that is already known (rows that an expert-parallel
  * dispatch has delivered to this GPU, Sec. 3.2.3: one local expert id per row, k = 1):
  * counts[e] = #{p : topk_idx[p] == e}, offsets = exclusive prefix sum, offsets[E] = n_pairs.

@@ -7,6 +7,7 @@
 // an LDS histogram of the experts it selected and writes it to its own row of the
 // workspace; a second one-block kernel sums the rows (counts) and prefix-scans them
 // (offsets).  No float atomics, no global atomics: the result is deterministic.
+#include <mutex>
 #include "moe_common.h"
 
 namespace moe {
@@ -218,6 +219,39 @@ static int route_blocks(int T) {
   return b < 1 ? 1 : (b > kRouteMaxBlocks ? kRouteMaxBlocks : b);
 }
 
+// ---- scratch of the entry point that takes no workspace -----------------------------------------------
+// moe_route_topk_noalloc keeps the per-workgroup histograms in this array instead of a caller's workspace.
+// Every GPU the library runs on holds its own copy (2 MiB) at its own address until the process ends.  In host
+// code the array's name is only a handle: the device address comes from hipGetSymbolAddress, once per device
+// with that device current, and that pointer is what the kernels are given.
+constexpr int kStaticHistInts = 1 << 19;
+static __device__ __align__(256) int32_t scratch[kStaticHistInts];
+
+constexpr int kMaxScratchDevices = 64;
+static std::mutex g_scratch_mutex;
+static int32_t* g_scratch_ptr[kMaxScratchDevices] = {};
+
+// device address of `scratch` on the current device (null + message on failure)
+static int32_t* scratch_on_current_device(const char* who) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) {
+    fail(MOE_ERR_HIP, "%s: cannot identify the current device (%s)", who, hipGetErrorString(err));
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || !p) {
+      fail(MOE_ERR_HIP, "%s: hipGetSymbolAddress of the static scratch failed on device %d (%s)", who, dev, hipGetErrorString(err));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  return g_scratch_ptr[dev];
+}
+
 static int32_t check_route_dims(int T, int E, int k) {
   MOE_REQUIRE(T >= 0 && E > 0 && k > 0, MOE_ERR_INVALID_ARG, "route: need T >= 0, E > 0, k > 0 (T=%d E=%d k=%d)", T, E, k);
   MOE_REQUIRE(k <= E, MOE_ERR_INVALID_ARG, "route: k=%d exceeds E=%d", k, E);
@@ -237,18 +271,11 @@ extern "C" size_t moe_route_topk_workspace_bytes(int T, int E, int k) {
   return align_up(static_cast<size_t>(route_blocks(T)) * E * sizeof(int32_t), 256);
 }
 
-extern "C" int32_t moe_route_topk(const float* logits, int T, int E, int k, int renorm,
-                                  int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
-                                  void* ws, size_t ws_bytes, void* stream) {
-  if (int32_t rc = check_route_dims(T, E, k)) return rc;
-  MOE_REQUIRE(counts && offsets, MOE_ERR_INVALID_ARG, "route: counts/offsets must not be null");
-  MOE_REQUIRE(T == 0 || (logits && topk_idx && topk_w), MOE_ERR_INVALID_ARG, "route: null logits/topk_idx/topk_w");
-  MOE_REQUIRE(ws && ws_bytes >= moe_route_topk_workspace_bytes(T, E, k) && aligned16(ws), MOE_ERR_WORKSPACE,
-              "route: workspace null, misaligned or smaller than %zu bytes", moe_route_topk_workspace_bytes(T, E, k));
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  begin_call("moe_route_topk", s);
+// the two launches of the routing call; hist: route_blocks(T) rows of E counters, every one of them written by
+// the first kernel before the second reads it (nothing has to be cleared)
+static void launch_route_topk(const float* logits, int T, int E, int k, int renorm, int32_t* topk_idx, float* topk_w,
+                              int32_t* counts, int32_t* offsets, int32_t* hist, hipStream_t s) {
   const int nblk = route_blocks(T);
-  int32_t* hist = static_cast<int32_t*>(ws);
   const int vpl = ceil_div(E, 64);
 #define MOE_LAUNCH_ROUTE(V) \
   MOE_LAUNCH("route_topk", route_topk_kernel<V>, dim3(nblk), dim3(kRouteThreads), 0, s, logits, T, E, k, renorm, topk_idx, topk_w, hist)
@@ -261,6 +288,39 @@ extern "C" int32_t moe_route_topk(const float* logits, int T, int E, int k, int 
   int epad = 64;
   while (epad < E) epad <<= 1;
   MOE_LAUNCH("route_scan", route_scan_kernel, dim3(1), dim3(1024), 0, s, hist, nblk, E, epad, counts, offsets);
+}
+
+extern "C" int32_t moe_route_topk(const float* logits, int T, int E, int k, int renorm,
+                                  int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_route_dims(T, E, k)) return rc;
+  MOE_REQUIRE(counts && offsets, MOE_ERR_INVALID_ARG, "route: counts/offsets must not be null");
+  MOE_REQUIRE(T == 0 || (logits && topk_idx && topk_w), MOE_ERR_INVALID_ARG, "route: null logits/topk_idx/topk_w");
+  MOE_REQUIRE(ws && ws_bytes >= moe_route_topk_workspace_bytes(T, E, k) && aligned16(ws), MOE_ERR_WORKSPACE,
+              "route: workspace null, misaligned or smaller than %zu bytes", moe_route_topk_workspace_bytes(T, E, k));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_route_topk", s);
+  launch_route_topk(logits, T, E, k, renorm, topk_idx, topk_w, counts, offsets, static_cast<int32_t*>(ws), s);
+  return end_call();
+}
+
+extern "C" size_t moe_route_topk_noalloc_max_bytes(void) { return static_cast<size_t>(kStaticHistInts) * sizeof(int32_t); }
+
+extern "C" int32_t moe_route_topk_noalloc(const float* logits, int T, int E, int k, int renorm,
+                                          int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
+                                          void* stream) {
+  if (int32_t rc = check_route_dims(T, E, k)) return rc;
+  MOE_REQUIRE(counts && offsets, MOE_ERR_INVALID_ARG, "route_noalloc: counts/offsets must not be null");
+  MOE_REQUIRE(T == 0 || (logits && topk_idx && topk_w), MOE_ERR_INVALID_ARG, "route_noalloc: null logits/topk_idx/topk_w");
+  const size_t need = moe_route_topk_workspace_bytes(T, E, k);
+  MOE_REQUIRE(need <= moe_route_topk_noalloc_max_bytes(), MOE_ERR_UNSUPPORTED,
+              "route_noalloc: T=%d, E=%d needs %zu bytes of histogram rows, the static scratch holds %zu; "
+              "use moe_route_topk with a workspace", T, E, need, moe_route_topk_noalloc_max_bytes());
+  int32_t* hist = scratch_on_current_device("route_noalloc");
+  if (!hist) return MOE_ERR_HIP;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  begin_call("moe_route_topk_noalloc", s);
+  launch_route_topk(logits, T, E, k, renorm, topk_idx, topk_w, counts, offsets, hist, s);
   return end_call();
 }
 

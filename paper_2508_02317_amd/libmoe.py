@@ -21,6 +21,7 @@ MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = [
     "moe_version", "moe_last_error",
     "moe_route_topk_workspace_bytes", "moe_route_topk", "moe_route_topk_bwd",
+    "moe_route_topk_noalloc_max_bytes", "moe_route_topk_noalloc",
     "moe_expert_offsets_workspace_bytes", "moe_expert_offsets",
     "moe_permute_workspace_bytes", "moe_permute",
     "moe_grouped_gemm_swiglu_fwd_workspace_bytes", "moe_grouped_gemm_swiglu_fwd",
@@ -58,6 +59,10 @@ def _load():
     lib.moe_route_topk_workspace_bytes.argtypes = [i32, i32, i32]
     lib.moe_route_topk.restype = ctypes.c_int32
     lib.moe_route_topk.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_route_topk_noalloc_max_bytes.restype = sz
+    lib.moe_route_topk_noalloc_max_bytes.argtypes = []
+    lib.moe_route_topk_noalloc.restype = ctypes.c_int32
+    lib.moe_route_topk_noalloc.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.moe_route_topk_bwd.restype = ctypes.c_int32
     lib.moe_route_topk_bwd.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
     lib.moe_expert_offsets_workspace_bytes.restype = sz
@@ -166,6 +171,17 @@ def moe_route_topk(logits, k, renorm=1, out=None, ws=None):
     ws, nbytes = _ws(lib.moe_route_topk_workspace_bytes(T, E, k), ws, dev)
     _check(lib.moe_route_topk(_ptr(logits), T, E, k, int(renorm), _ptr(idx), _ptr(w), _ptr(counts), _ptr(offsets),
                               _ptr(ws), nbytes, _stream()))
+    return idx, w, counts, offsets
+
+
+def moe_route_topk_noalloc(logits, k, renorm, out):
+    """moe_route_topk without a workspace (histogram rows in the library's static device array); `out` =
+    (topk_idx, topk_w, counts, offsets) must be given: nothing is allocated here either."""
+    _need(logits, torch.float32, "logits")
+    T, E = logits.shape
+    idx, w, counts, offsets = out
+    _check(lib.moe_route_topk_noalloc(_ptr(logits), T, E, k, int(renorm), _ptr(idx), _ptr(w), _ptr(counts), _ptr(offsets),
+                                      _stream()))
     return idx, w, counts, offsets
 
 

@@ -43,7 +43,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kXcds = 8;
 
 // ---- tile shapes ------------------------------------------------------------------------------
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_>
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int STAGES_A_, int STAGES_B_>
 struct Tile {
   static constexpr int BM = BM_, BN = BN_, BK = BK_;
   static constexpr int WGM = WGM_, WGN = WGN_;            // grid of wavefronts over the tile
@@ -51,16 +51,20 @@ struct Tile {
   static constexpr int WM = BM / WGM, WN = BN / WGN;      // sub-tile of one wavefront
   static constexpr int MI = WM / 32, NI = WN / 32;        // MFMA tiles per wave
   static constexpr int kABytes = BM * BK * 2, kBBytes = BN * BK * 2;
-  static constexpr int kStageBytes = kABytes + kBBytes;
-  static constexpr int kStages = STAGES_;                 // LDS ring: one slab being read, the others in flight
-  static constexpr int kLdsBytes = kStages * kStageBytes;
-  // Epilogue staging strips (one per wave, 32 rows x (WN + 4) floats).  With a two-stage ring and room in the
-  // 160 KiB of LDS they sit behind the first stage, so that stage can already take the first slab of the
-  // workgroup's next tile while the epilogue runs; otherwise they reuse the ring from its start.
+  // LDS ring: each operand has its own ring of slab buffers (SA for the row side, SB for the column side); slab kt
+  // lives in buffer kt % SA and kt % SB.  One slab is being multiplied, the others are in flight.  With 64 KiB per
+  // slab only 2.5 slabs fit the 160 KiB of a CU: SA = 2, SB = 3, which is what keeps the CU's window of outstanding
+  // L2 requests full across the barrier that separates two slabs (with 2 + 2 it drains at every slab).  The deeper
+  // ring goes to the side with fewer fragments per wave: its third buffer lies beyond the 16-bit immediate offset of
+  // the LDS instructions and costs one more address register per fragment.
+  static constexpr int SA = STAGES_A_, SB = STAGES_B_;
+  static constexpr int kBBase = SA * kABytes;             // the column side's buffers follow the row side's
+  static constexpr int kLdsBytes = SA * kABytes + SB * kBBytes;
+  // Epilogue staging strips (one per wave, 32 rows x (WN + 4) floats) reuse the ring from its start once it is idle.
   static constexpr int kStripBytes = 32 * (WN + 4) * 4;
-  static constexpr bool kStripsBehindStage0 = kStages == 2 && kStageBytes + kWaves * kStripBytes <= 156 * 1024;
-  static constexpr int kStripBase = kStripsBehindStage0 ? kStageBytes : 0;
-  static constexpr int kLdsAlloc = kStripBase + kWaves * kStripBytes > kLdsBytes ? kStripBase + kWaves * kStripBytes : kLdsBytes;
+  static constexpr int kStripBase = 0;
+  static constexpr int kLdsAlloc = kWaves * kStripBytes > kLdsBytes ? kWaves * kStripBytes : kLdsBytes;
+  static_assert(kLdsAlloc <= 160 * 1024, "a CU has 160 KiB of LDS");
   static constexpr int kBlocksPerCu = 2 * kLdsAlloc <= 160 * 1024 ? 2 : 1;   // by LDS capacity
   static constexpr int kWavesPerSimd = kBlocksPerCu * kWaves / 4;
 };
@@ -113,15 +117,29 @@ __device__ __forceinline__ int frag_off(int row_base, int kk, int lane) {
     return ks_off<ROWS>(k, col >> 3) + (col & 4) * 2;                     // 8-byte half of the piece
   }
 }
-template <bool KS, int ROWS>
-__device__ __forceinline__ bf16x8 read_frag(const char* p) {
+// One fragment from the operand buffer that starts IMM bytes into the ring (a compile-time constant: buffer and
+// reduction step), at this lane's offset `off` (its fragment offset, already adjusted for the step if k-contiguous).
+//
+// The transposing read is issued as an assembly statement on purpose.  The compiler orders every LDS read it knows
+// to be one behind all outstanding direct global->LDS loads (it cannot tell which bytes they will write), i.e. it
+// puts a wait for *all* of this wave's loads in front of the first transposing read of every slab -- which
+// serialises the ring: the slabs just requested would have to land before the slab in hand may be read.  The ring
+// needs no such wait: a buffer is read only after the counted wait and the barrier that follow its own loads, and
+// the results are consumed only after the explicit wait for the LDS counter in the slab loop.  (Plain 16-byte
+// loads are not held back that way.)
+template <bool KS, int ROWS, int IMM>
+__device__ __forceinline__ bf16x8 read_frag(const char* ring, uint32_t ring_lds, int off) {
   if constexpr (!KS) {
-    return *reinterpret_cast<const bf16x8*>(p);
+    return *reinterpret_cast<const bf16x8*>(ring + IMM + off);
   } else {
-    typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
     // k + 4 has the same swizzle (k & 3 unchanged): a constant 4 k-rows further
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * ROWS * 2));
+    constexpr int HI = 4 * ROWS * 2;
+    constexpr int FAR = IMM + HI >= 65536 ? 65536 : 0;     // beyond the 16-bit offset field: moved into the address
+    static_assert(IMM - FAR >= 0 && IMM + HI - FAR < 65536, "operand buffers lie within 128 KiB of the ring start");
+    const uint32_t addr = ring_lds + static_cast<uint32_t>(off) + FAR;
+    bf16x4 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(IMM - FAR));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(IMM + HI - FAR));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 }
@@ -272,14 +290,15 @@ template <int n> __device__ __forceinline__ void wait_vmcnt() {
 // s_waitcnt that waits only for the LDS / scalar-memory counter to reach zero
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14)); }
 
-// wait until at most `slabs` slabs' worth of this wave's direct loads are still in flight
-template <int L, int MAXS>
-__device__ __forceinline__ void wait_slabs_in_flight(int slabs) {
-  if constexpr (MAXS == 0) {
+// wait until at most n of this wave's direct loads are still in flight; n is a multiple of STEP and at most MAX
+// (the hardware wait takes an immediate: one comparison per candidate, the steady-state value first)
+template <int MAX, int STEP>
+__device__ __forceinline__ void wait_loads_in_flight(int n) {
+  if constexpr (MAX <= 0) {
     wait_vmcnt<0>();
   } else {
-    if (slabs >= MAXS) wait_vmcnt<MAXS * L>();
-    else wait_slabs_in_flight<L, MAXS - 1>(slabs);
+    if (n >= MAX) wait_vmcnt<MAX>();
+    else wait_loads_in_flight<MAX - STEP, STEP>(n);
   }
 }
 
@@ -293,24 +312,36 @@ template <class T> struct FragOffsets {
   int a[T::MI];
   int b[T::NI];
 };
-// Offset of the same fragment at step kk (a compile-time constant in the unrolled loop).  k-strided tile: 16
-// reduction rows further, and the swizzle (k & 3) is unchanged.  k-contiguous tile: the step moves the piece
-// index by 2*kk, and because the piece index is XORed with the row's swizzle, so is the offset: one XOR of bits
-// above the 16-byte piece and below the row pitch.  One register per fragment instead of one per (fragment, step).
-template <bool KS, int ROWS, int BK>
-__device__ __forceinline__ int frag_step(int off0, int kk) {
-  static_assert((BK / 16 - 1) * 32 < BK * 2, "the step bits must lie inside a row");
-  if constexpr (KS) return off0 + kk * 16 * ROWS * 2;
-  else return off0 ^ (kk << 5);
+// The same fragment at reduction step KK.  k-strided tile: 16 reduction rows further (a constant number of bytes, the
+// swizzle k & 3 is unchanged).  k-contiguous tile: the step moves the piece index by 2*KK, and because the piece
+// index is XORed with the row's swizzle, so is the offset: one XOR of bits above the 16-byte piece and below the
+// row pitch.  One register per fragment instead of one per (fragment, step).
+// OFF_A / OFF_B: where the slab's buffers start in the ring.
+template <class T, bool A_KS, bool B_KS, int OFF_A, int OFF_B, int KK>
+__device__ __forceinline__ void load_frags(Frags<T>& f, const char* ring, uint32_t ring_lds, const FragOffsets<T>& fo) {
+  static_assert((T::BK / 16 - 1) * 32 < T::BK * 2, "the step bits must lie inside a row");
+  constexpr int IMM_A = OFF_A + (A_KS ? KK * 16 * T::BM * 2 : 0), IMM_B = OFF_B + (B_KS ? KK * 16 * T::BN * 2 : 0);
+#pragma unroll
+  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM, IMM_A>(ring, ring_lds, A_KS ? fo.a[i] : fo.a[i] ^ (KK << 5));
+#pragma unroll
+  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN, IMM_B>(ring, ring_lds, B_KS ? fo.b[i] : fo.b[i] ^ (KK << 5));
+}
+// Wait until this wave's LDS reads have delivered, with the fragments as operands of the wait: the registers a
+// transposing read (an assembly statement, see read_frag) is filling stay reserved until here on every path --
+// the compiler must neither reuse them earlier nor move a consumer above the wait.
+template <class T>
+__device__ __forceinline__ void settle(Frags<T>& f) {
+  static_assert(T::MI + T::NI <= 8, "one operand per fragment");
+  if constexpr (T::MI == 4 && T::NI == 2) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.a[2]), "+v"(f.a[3]), "+v"(f.b[0]), "+v"(f.b[1]));
+  } else if constexpr (T::MI == 2 && T::NI == 2) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.b[0]), "+v"(f.b[1]));
+  } else {
+    static_assert(T::MI == 1 && T::NI == 2, "add the operand list of this wave shape");
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.b[0]), "+v"(f.b[1]));
+  }
 }
 
-template <class T, bool A_KS, bool B_KS>
-__device__ __forceinline__ void load_frags(Frags<T>& f, const char* stage, const FragOffsets<T>& fo, int kk) {
-#pragma unroll
-  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM>(stage + frag_step<A_KS, T::BM, T::BK>(fo.a[i], kk));
-#pragma unroll
-  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN>(stage + T::kABytes + frag_step<B_KS, T::BN, T::BK>(fo.b[i], kk));
-}
 // MFMAs number FROM .. TO-1 (row-major over the wave's MI x NI fragments) of one reduction step
 template <class T, int FROM, int TO>
 __device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::NI]) {
@@ -326,43 +357,73 @@ __device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::N
 // only in their base pointers).  a_row[mi] / b_row[ni]: first tile row of the wave's mi-th / ni-th
 // 32-row fragment.
 //
-// Slabs stream through an S-stage LDS ring filled by direct global->LDS loads, and the MFMA
-// operands are double-buffered in registers, so that every LDS read is issued one reduction step
-// ahead of the MFMAs that consume it.  Per slab kt:
+// Slabs stream through the two LDS rings (SA buffers for the A side, SB <= SA for the B side) filled by direct
+// global->LDS loads, and the MFMA operands are double-buffered in registers, so that every LDS read is issued
+// one reduction step ahead of the MFMAs that consume it.  Per slab kt:
 //     read step 1.. of slab kt (into the other register set) | MFMAs of the steps already loaded
-//     wait: own LDS reads of slab kt complete, own loads of slab kt+1 landed
-//     barrier: slab kt+1 is visible to all, and nobody reads the stage of slab kt any more
-//     refill that stage with slab kt+S; read step 0 of slab kt+1 | MFMAs of the last step of slab kt
-// so up to S-1 slabs are in flight behind the slab being multiplied.  The loop over slabs is
-// unrolled S times so that every LDS address is "register + constant" and no address arithmetic
-// competes with the MFMAs for issue slots.  What limits the stream is the number of L2 requests a
-// CU can have outstanding (about 128, whatever the ring depth): 64-byte row pieces (BK = 32) give
-// about 30 bytes per clock and CU on L2 hits, 128-byte pieces (BK = 64) about 60.
+//     wait: own LDS reads of slab kt complete, own loads of slab kt+1 landed (later slabs stay in flight)
+//     barrier: slab kt+1 is visible to all, and nobody reads the buffers of slab kt any more
+//     refill them with B of slab kt+SB, then A of slab kt+SA; read step 0 of slab kt+1 | MFMAs of the last step
+// Loads complete in the order they were enqueued, and the refill enqueues the slab that is needed first first, so
+// "slab kt+1 has landed" is a wait for all but the loads enqueued after it -- an immediate count.  The loop over
+// slabs is unrolled lcm(SA, SB) times so that every LDS address is "register + constant" and no address arithmetic
+// competes with the MFMAs for issue slots.  What limits the stream is the number of L2 requests a CU can have
+// outstanding (about 128 lines, whatever is in flight in the rings): 64-byte row pieces (BK = 32) give about
+// 30 bytes per clock and CU on L2 hits, 128-byte pieces (BK = 64) about 60; the rings only have to keep that
+// window full, which a ring that drains at every slab (SA = SB = 2) does not.
 template <class T, bool A_KS, bool B_KS, bool A_GATHER = false, bool B_GATHER = false>
 struct MainLoop {
   typedef Dma<A_KS, T::BM, T::BK, T::kWaves, A_GATHER> DmaA;
   typedef Dma<B_KS, T::BN, T::BK, T::kWaves, B_GATHER> DmaB;
-  static constexpr int L = DmaA::N + DmaB::N;          // loads per thread per slab
-  static constexpr int S = T::kStages;
+  static constexpr int NA = DmaA::N, NB = DmaB::N;     // loads per thread per slab and side
+  static constexpr int SA = T::SA, SB = T::SB;
+  static_assert(SA >= 2 && SB >= 2, "one slab being multiplied, at least one in flight");
+  static constexpr int U = (SA % SB == 0) ? SA : SA * SB;   // slabs per unrolled trip: buffer indices are compile-time
   static constexpr int STEPS = T::BK / 16;             // reduction steps per slab (even)
-  static_assert((S - 1) * L < 64, "vmcnt is a 6-bit counter");
+  static constexpr int kMaxAhead = (SA - 1) * NA + (SB - 1) * NB;   // most loads ever in flight behind slab 0
+  static constexpr int kStep = NA == NB ? NA : 1;
+  static_assert(kMaxAhead < 64, "vmcnt is a 6-bit counter");
 
   DmaA da;
   DmaB db;
   FragOffsets<T> fo;
   Frags<T> f0, f1;                                     // even / odd reduction steps
   char* lds;
+  uint32_t lds32;                                      // the ring's start as an LDS address
   const char* zeros;
   int nslabs, nfull, K, wave;
 
-  __device__ __forceinline__ void issue(int slab, int stage) {
-    char* st = lds + stage * T::kStageBytes;
-    if (slab < nfull) {
-      da.issue(slab, st, wave);
-      db.issue(slab, st + T::kABytes, wave);
-    } else {
-      da.issue_tail(slab, K, zeros, st, wave);
-      db.issue_tail(slab, K, zeros, st + T::kABytes, wave);
+  __device__ __forceinline__ char* buf_a(int stage) const { return lds + stage * T::kABytes; }
+  __device__ __forceinline__ char* buf_b(int stage) const { return lds + T::kBBase + stage * T::kBBytes; }
+  // LDS reads: the B side's fragment offsets already contain kBBase, so that every buffer but the last of a
+  // three-deep ring is reached with the 16-bit immediate offset of the LDS instruction
+  __device__ __forceinline__ void issue_a(int slab, int stage) {
+    if (slab < nfull) da.issue(slab, buf_a(stage), wave);
+    else da.issue_tail(slab, K, zeros, buf_a(stage), wave);
+  }
+  __device__ __forceinline__ void issue_b(int slab, int stage) {
+    if (slab < nfull) db.issue(slab, buf_b(stage), wave);
+    else db.issue_tail(slab, K, zeros, buf_b(stage), wave);
+  }
+  // loads enqueued so far for slabs beyond kt + 1 (they may stay in flight when slab kt + 1 is needed)
+  __device__ __forceinline__ int loads_beyond(int kt) const {
+    const int rest = nslabs - 2 - kt;                  // slabs that exist beyond kt + 1
+    return max(0, min(SA - 2, rest)) * NA + max(0, min(SB - 2, rest)) * NB;
+  }
+
+  // Steps KK .. STEPS-2 of the slab in buffers SGA / SGB.  Every step first waits for its own operands, then issues
+  // the LDS reads of the next step and only then its MFMAs, so each read has a whole step of MFMAs (plus the other
+  // wave on the SIMD) to complete.  Even steps multiply f0, odd steps f1.
+  template <int SGA, int SGB, int KK>
+  __device__ __forceinline__ void steps(f32x16 (&acc)[T::MI][T::NI]) {
+    if constexpr (KK + 1 < STEPS) {
+      settle<T>((KK & 1) ? f1 : f0);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags<T, A_KS, B_KS, SGA * T::kABytes, SGB * T::kBBytes, KK + 1>((KK & 1) ? f0 : f1, lds, lds32, fo);
+      __builtin_amdgcn_sched_barrier(0);
+      mma<T, 0, T::MI * T::NI>((KK & 1) ? f1 : f0, acc);
+      __builtin_amdgcn_sched_barrier(0);
+      steps<SGA, SGB, KK + 1>(acc);
     }
   }
 
@@ -370,32 +431,27 @@ struct MainLoop {
   // row segment) only takes part in the loads and barriers; its SIMD time goes to the other waves.
   template <int STG, bool ACTIVE>
   __device__ __forceinline__ void slab_body(int kt, f32x16 (&acc)[T::MI][T::NI]) {
-    constexpr int NXT = (STG + 1) % S;
-    const char* buf = lds + STG * T::kStageBytes;
-    // Every step first waits for its own operands, then issues the LDS reads of the next step and only
-    // then its MFMAs, so each read has a whole step of MFMAs (plus the other wave on the SIMD) to complete.
+    constexpr int SGA = STG % SA, SGB = STG % SB, NXA = (STG + 1) % SA, NXB = (STG + 1) % SB;
     constexpr int ALL = T::MI * T::NI;
     if constexpr (ACTIVE) {
-#pragma unroll
-      for (int kk = 0; kk + 1 < STEPS; ++kk) {         // every step but the last: fetch the next step, multiply this one
-        wait_lgkmcnt0();
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags<T, A_KS, B_KS>((kk & 1) ? f0 : f1, buf, fo, kk + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma<T, 0, ALL>((kk & 1) ? f1 : f0, acc);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      wait_lgkmcnt0();                                 // last step is in f1; this wave no longer needs the stage of slab kt
+      steps<SGA, SGB, 0>(acc);                         // every step but the last: fetch the next step, multiply this one
+      settle<T>(f1);                                   // last step is in f1; this wave no longer needs the buffers of slab kt
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (kt + 1 < nslabs) wait_slabs_in_flight<L, S - 2>(nslabs - 2 - kt);   // slab kt+1 has landed
+    if (kt + 1 < nslabs) wait_loads_in_flight<(SA - 2) * NA + (SB - 2) * NB, kStep>(loads_beyond(kt));   // slab kt+1 has landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (ACTIVE) {
-      if (kt + 1 < nslabs) load_frags<T, A_KS, B_KS>(f0, lds + NXT * T::kStageBytes, fo, 0);
+      if (kt + 1 < nslabs) load_frags<T, A_KS, B_KS, NXA * T::kABytes, NXB * T::kBBytes, 0>(f0, lds, lds32, fo);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (kt + S < nslabs) issue(kt + S, STG);
+    if constexpr (SB <= SA) {                          // the side whose slab is needed sooner goes first
+      if (kt + SB < nslabs) issue_b(kt + SB, SGB);
+      if (kt + SA < nslabs) issue_a(kt + SA, SGA);
+    } else {
+      if (kt + SA < nslabs) issue_a(kt + SA, SGA);
+      if (kt + SB < nslabs) issue_b(kt + SB, SGB);
+    }
     if constexpr (ACTIVE) {
       __builtin_amdgcn_sched_barrier(0);
       mma<T, 0, ALL>(f1, acc);
@@ -404,7 +460,7 @@ struct MainLoop {
 
   template <int STG, bool ACTIVE>
   __device__ __forceinline__ void run_from(int& kt, f32x16 (&acc)[T::MI][T::NI]) {
-    if constexpr (STG < S) {
+    if constexpr (STG < U) {
       if (kt < nslabs) {
         slab_body<STG, ACTIVE>(kt, acc);
         ++kt;
@@ -415,13 +471,14 @@ struct MainLoop {
 
   template <bool ACTIVE>
   __device__ __forceinline__ void stream(f32x16 (&acc)[T::MI][T::NI]) {
-    if constexpr (ACTIVE) load_frags<T, A_KS, B_KS>(f0, lds, fo, 0);
+    if constexpr (ACTIVE) load_frags<T, A_KS, B_KS, 0, 0, 0>(f0, lds, lds32, fo);
     int kt = 0;
 #pragma nounroll
-    while (kt + S <= nslabs) {                         // S slabs per trip: stages are compile-time
+    while (kt + U <= nslabs) {                         // U slabs per trip: buffers are compile-time
       run_from<0, ACTIVE>(kt, acc);
     }
-    run_from<0, ACTIVE>(kt, acc);                      // the remaining < S slabs
+    run_from<0, ACTIVE>(kt, acc);                      // the remaining < U slabs
+    if constexpr (ACTIVE) settle<T>(f0);               // nothing is in flight into a register when the epilogue starts
   }
 
   // reduction length, LDS ring and the per-lane fragment offsets of this wave's sub-tile
@@ -430,34 +487,35 @@ struct MainLoop {
     const int tid = threadIdx.x, lane = tid & 63;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS destinations stay scalar
     lds = lds_; zeros = reinterpret_cast<const char*>(zeros_); K = K_;
+    lds32 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)lds_));
     nfull = K > 0 ? K / T::BK : 0;
     nslabs = K > 0 ? (K + T::BK - 1) / T::BK : 0;
 #pragma unroll
     for (int i = 0; i < T::MI; ++i) fo.a[i] = frag_off<A_KS, T::BM, T::BK>(a_row[i], 0, lane);
 #pragma unroll
-    for (int i = 0; i < T::NI; ++i) fo.b[i] = frag_off<B_KS, T::BN, T::BK>(b_row[i], 0, lane);
+    for (int i = 0; i < T::NI; ++i) fo.b[i] = T::kBBase + frag_off<B_KS, T::BN, T::BK>(b_row[i], 0, lane);
   }
-  // enqueue slabs [FIRST, LAST) of a segment into their stages; FIRST == 0 also points the loads at the operands.
-  // The ring must be idle from stage FIRST on.  Slabs are enqueued in order, whatever else the caller does between.
-  template <int FIRST, int LAST>
+  // point the loads at the operands of a segment and fill both rings, slab by slab (A before B), as far as they go.
+  // The rings must be idle.
   __device__ __forceinline__ void start(const Operand& oa, const Operand& ob) {
-    if constexpr (FIRST == 0) {
-      const int lane = threadIdx.x & 63;
-      da.init(oa, wave, lane);
-      db.init(ob, wave, lane);
-    }
+    const int lane = threadIdx.x & 63;
+    da.init(oa, wave, lane);
+    db.init(ob, wave, lane);
 #pragma unroll
-    for (int s0 = FIRST; s0 < LAST; ++s0)
-      if (s0 < nslabs) issue(s0, s0);
+    for (int s0 = 0; s0 < (SA > SB ? SA : SB); ++s0) {
+      if (s0 < SA && s0 < nslabs) issue_a(s0, s0);
+      if (s0 < SB && s0 < nslabs) issue_b(s0, s0);
+    }
   }
-  // multiply the segment whose first S slabs have been enqueued
+  // multiply the segment whose first slabs have been enqueued by start()
   __device__ __forceinline__ void go(bool active, f32x16 (&acc)[T::MI][T::NI]) {
     if (nslabs <= 0) return;
-    wait_slabs_in_flight<L, S - 1>(nslabs - 1);        // slab 0 has landed
+    const int rest = nslabs - 1;                       // slabs beyond slab 0 that start() enqueued
+    wait_loads_in_flight<kMaxAhead, kStep>(min(SA - 1, rest) * NA + min(SB - 1, rest) * NB);   // slab 0 has landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     if (active) stream<true>(acc); else stream<false>(acc);
-    __syncthreads();                                   // all reads done before anything refills the ring
+    __syncthreads();                                   // all reads done before anything refills the rings
   }
 
   __device__ __forceinline__ void run(const Operand* opA, const Operand* opB, int nseg, int K_, char* lds_,
@@ -482,7 +540,7 @@ struct MainLoop {
       ob.valid[1] = opB[0].valid[1];
       ob.gather = opB[0].gather;
       ob.grow = opB[0].grow;
-      start<0, S>(oa, ob);
+      start(oa, ob);
       go(active, acc);
     }
   }
@@ -1068,7 +1126,7 @@ struct WgradArgs {
 // Column tiles one workgroup of a weight-gradient product takes in turn (see the kernel).  Measured in the layer
 // step: two for [dW_gate; dW_up] (7 % faster at 512 rows per expert, no change at 2560), one for dW_down (with two
 // or all three of its column tiles per workgroup it is 15-40 % slower).
-template <class T, int WHICH> constexpr int kWgradSpan = (T::kStripsBehindStage0 && WHICH == 1) ? 2 : 1;
+template <class T, int WHICH> constexpr int kWgradSpan = (T::kWaves == 8 && T::BM == 256 && WHICH == 1) ? 2 : 1;
 
 // WHICH 0: dW_down, 1: [dW_gate; dW_up], 2: router (separate symbols so profiles tell them apart).
 // GATHER: the operand that holds one row per token -- lhs for WHICH 0 (the output gradient), rhs for WHICH 1
@@ -1139,7 +1197,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
   MainLoop<T, true, true, GA, GB> ml;
   ml.prepare(end - begin, lds, p.zeros, a_row, b_row);
   point_b(nt0);
-  ml.template start<0, T::kStages>(opA, opB);
+  ml.start(opA, opB);
 
   float* strip = reinterpret_cast<float*>(lds + T::kStripBase + wave * Strip<T>::kBytes);
   constexpr int LPR = WN / 8;
@@ -1154,10 +1212,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     zero_acc<T>(acc);
     ml.go(true, acc);
     const bool more = t + 1 < SPAN && nt + 1 < p.tiles_n;
-    if (more) {                                        // the ring is idle: the next tile's first slab(s) can go
-      point_b(nt + 1);
-      if constexpr (T::kStripsBehindStage0) ml.template start<0, 1>(opA, opB);
-    }
+    if (more) point_b(nt + 1);
     const int el = not_before_here(lane);             // this lane, for the epilogue
     const int cl = wn * WN + (el % LPR) * 8;
     if (part) {                                        // chunk of a split expert: fp32 partial tile
@@ -1199,9 +1254,8 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
       }
     }
     if (more) {
-      __syncthreads();                                 // every wave is done with its strip: the rest of the ring may be refilled
-      if constexpr (T::kStripsBehindStage0) ml.template start<1, T::kStages>(opA, opB);
-      else ml.template start<0, T::kStages>(opA, opB);
+      __syncthreads();                                 // every wave is done with its strip: the rings may be refilled
+      ml.start(opA, opB);
     }
   }
 }
@@ -1242,9 +1296,9 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
 //     waves per SIMD cover that better -- 3-5 % faster on dW_down at every size and on [dW_gate; dW_up] from
 //     about 1000 rows per expert; the row products are 2-5 % slower with it and keep 8 waves.
 //   TileRouter: 64 x 128 x 64 for the skinny products with N = E, two workgroups per CU.
-typedef Tile<256, 256, 64, 2, 4, 2> TileBig;
-typedef Tile<256, 256, 64, 4, 4, 2> TileBigW16;
-typedef Tile<64, 128, 64, 2, 2, 3> TileRouter;
+typedef Tile<256, 256, 64, 2, 4, 2, 3> TileBig;
+typedef Tile<256, 256, 64, 4, 4, 2, 3> TileBigW16;
+typedef Tile<64, 128, 64, 2, 2, 3, 3> TileRouter;
 
 static int row_bm() { return TileBig::BM; }
 // bound used for workspace sizing: the smallest row tile gives the longest list

@@ -32,6 +32,7 @@
 #include <algorithm>
 #include <mutex>
 #include <type_traits>
+#include <utility>
 #include "moe_common.h"
 
 namespace moe {
@@ -117,29 +118,28 @@ __device__ __forceinline__ int frag_off(int row_base, int kk, int lane) {
     return ks_off<ROWS>(k, col >> 3) + (col & 4) * 2;                     // 8-byte half of the piece
   }
 }
-// One fragment from the operand buffer that starts IMM bytes into the ring (a compile-time constant: buffer and
-// reduction step), at this lane's offset `off` (its fragment offset, already adjusted for the step if k-contiguous).
-//
-// The transposing read is issued as an assembly statement on purpose.  The compiler orders every LDS read it knows
-// to be one behind all outstanding direct global->LDS loads (it cannot tell which bytes they will write), i.e. it
-// puts a wait for *all* of this wave's loads in front of the first transposing read of every slab -- which
-// serialises the ring: the slabs just requested would have to land before the slab in hand may be read.  The ring
-// needs no such wait: a buffer is read only after the counted wait and the barrier that follow its own loads, and
-// the results are consumed only after the explicit wait for the LDS counter in the slab loop.  (Plain 16-byte
-// loads are not held back that way.)
+// One fragment: 16 bytes per lane at LDS address `addr` + IMM (a compile-time constant: buffer, reduction step or
+// fragment).  Both kinds of read are assembly statements on purpose.
+//   * The compiler orders every LDS read it knows to be one behind all outstanding direct global->LDS loads (it
+//     cannot tell which bytes they will write): it puts a wait for *all* of this wave's loads in front of the first
+//     such read of every slab, which serialises the ring -- the slabs just requested would have to land before the
+//     slab in hand may be read.  The ring needs no such wait: a buffer is read only after the counted wait and the
+//     barrier that follow its own loads.
+//   * The address register and the 16-bit immediate are chosen here, so no address arithmetic is left in the slab
+//     loop (every vector instruction there takes issue slots from the MFMAs of both waves of the SIMD).
+// The results arrive asynchronously; they are consumed only after settle() below, which names them as operands.
 template <bool KS, int ROWS, int IMM>
-__device__ __forceinline__ bf16x8 read_frag(const char* ring, uint32_t ring_lds, int off) {
+__device__ __forceinline__ bf16x8 lds_read_frag(uint32_t addr) {
+  static_assert(IMM >= 0 && IMM + (KS ? 4 * ROWS * 2 : 0) < 65536, "the immediate offset of an LDS instruction has 16 bits");
   if constexpr (!KS) {
-    return *reinterpret_cast<const bf16x8*>(ring + IMM + off);
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(IMM));
+    return v;
   } else {
     // k + 4 has the same swizzle (k & 3 unchanged): a constant 4 k-rows further
-    constexpr int HI = 4 * ROWS * 2;
-    constexpr int FAR = IMM + HI >= 65536 ? 65536 : 0;     // beyond the 16-bit offset field: moved into the address
-    static_assert(IMM - FAR >= 0 && IMM + HI - FAR < 65536, "operand buffers lie within 128 KiB of the ring start");
-    const uint32_t addr = ring_lds + static_cast<uint32_t>(off) + FAR;
     bf16x4 lo, hi;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(IMM - FAR));
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(IMM + HI - FAR));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(IMM));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(IMM + 4 * ROWS * 2));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 }
@@ -260,12 +260,14 @@ template <bool KS, int ROWS, int BK, int WAVES, bool GATHER = false> struct Dma 
   // enqueue this wave's share of slab `slab` into the operand tile at `tile` (LDS); slabs are issued in order
   __device__ __forceinline__ void issue(int slab, char* tile, int wave) {
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const char* g = base[i] + slab * step + lane_off(i);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                       (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
-    }
+    for (int i = 0; i < N; ++i) issue_one(i, slab, tile, wave);
     fetch_rows(slab + 1);
+  }
+  // one of the N loads of a full slab (the caller enqueues all N, in order, then fetch_rows(slab + 1))
+  __device__ __forceinline__ void issue_one(int i, int slab, char* tile, int wave) {
+    const char* g = base[i] + slab * step + lane_off(i);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)(tile + (wave * N + i) * 1024), 16, 0, 0);
   }
   // the same for the last, partial slab: pieces whose reduction index is >= K read zeros
   __device__ __forceinline__ void issue_tail(int slab, int K, const char* zeros, char* tile, int wave) {
@@ -307,24 +309,42 @@ template <class T> struct Frags {
   bf16x8 a[T::MI];
   bf16x8 b[T::NI];
 };
-// per-lane LDS offsets of every fragment at reduction step 0, relative to the start of its operand tile
-template <class T> struct FragOffsets {
-  int a[T::MI];
-  int b[T::NI];
+// Per-lane LDS addresses of the fragments, set up once per tile.  The wave's fragments of one side lie a constant
+// number of tile rows apart (FR rows, normally 32), and
+//   * in a k-contiguous tile a fragment FR rows further is a constant number of bytes further (the swizzle of a row
+//     repeats every 16 rows), while the reduction step moves the piece index by 2*KK, which the swizzle turns into
+//     an XOR of the address: one register per step, the fragment in the immediate;
+//   * in a k-strided tile the step is a constant number of bytes (16 reduction rows; the swizzle k & 3 is unchanged)
+//     but a fragment 32 columns further is not (its 64-byte chunk index is XORed with k & 3): one register per
+//     fragment, the step in the immediate.
+// A buffer that starts 64 KiB or more into its side's ring is out of reach of the immediate: `far` holds the same
+// addresses 64 KiB further (only the third buffer of a three-deep ring needs them).
+template <class T, bool A_KS, bool B_KS> struct FragAddrs {
+  static constexpr int STEPS = T::BK / 16;
+  static constexpr int NA = A_KS ? T::MI : STEPS, NB = B_KS ? T::NI : STEPS;
+  static constexpr bool A_FAR = (T::SA - 1) * T::kABytes >= 65536, B_FAR = (T::SB - 1) * T::kBBytes >= 65536;
+  uint32_t a[NA], b[NB];
+  uint32_t a_far[A_FAR ? NA : 1], b_far[B_FAR ? NB : 1];
 };
-// The same fragment at reduction step KK.  k-strided tile: 16 reduction rows further (a constant number of bytes, the
-// swizzle k & 3 is unchanged).  k-contiguous tile: the step moves the piece index by 2*KK, and because the piece
-// index is XORed with the row's swizzle, so is the offset: one XOR of bits above the 16-byte piece and below the
-// row pitch.  One register per fragment instead of one per (fragment, step).
-// OFF_A / OFF_B: where the slab's buffers start in the ring.
-template <class T, bool A_KS, bool B_KS, int OFF_A, int OFF_B, int KK>
-__device__ __forceinline__ void load_frags(Frags<T>& f, const char* ring, uint32_t ring_lds, const FragOffsets<T>& fo) {
+// Fragment I of one side at reduction step KK, from the buffer that starts OFF bytes into the side's ring; FR: tile
+// rows between the wave's fragments; near / far: the side's address registers.
+template <bool KS, int ROWS, int BK, int FR, int OFF, int KK, int I, int N>
+__device__ __forceinline__ bf16x8 read_side(const uint32_t (&near)[N], const uint32_t* far) {
+  constexpr int FAR = OFF >= 65536 ? 65536 : 0;
+  if constexpr (KS) return lds_read_frag<true, ROWS, OFF - FAR + KK * 16 * ROWS * 2>(FAR ? far[I] : near[I]);
+  else return lds_read_frag<false, ROWS, OFF - FAR + I * FR * BK * 2>(FAR ? far[KK] : near[KK]);
+}
+template <class T, bool A_KS, bool B_KS, int FRA, int FRB, int OFF_A, int OFF_B, int KK, int... IA, int... IB>
+__device__ __forceinline__ void load_frags_seq(Frags<T>& f, const FragAddrs<T, A_KS, B_KS>& fa, std::integer_sequence<int, IA...>,
+                                               std::integer_sequence<int, IB...>) {
+  ((f.a[IA] = read_side<A_KS, T::BM, T::BK, FRA, OFF_A, KK, IA>(fa.a, fa.a_far)), ...);
+  ((f.b[IB] = read_side<B_KS, T::BN, T::BK, FRB, OFF_B, KK, IB>(fa.b, fa.b_far)), ...);
+}
+// OFF_A / OFF_B: where the slab's buffers start in their side's ring; FRA / FRB: tile rows between the wave's fragments.
+template <class T, bool A_KS, bool B_KS, int FRA, int FRB, int OFF_A, int OFF_B, int KK>
+__device__ __forceinline__ void load_frags(Frags<T>& f, const FragAddrs<T, A_KS, B_KS>& fa) {
   static_assert((T::BK / 16 - 1) * 32 < T::BK * 2, "the step bits must lie inside a row");
-  constexpr int IMM_A = OFF_A + (A_KS ? KK * 16 * T::BM * 2 : 0), IMM_B = OFF_B + (B_KS ? KK * 16 * T::BN * 2 : 0);
-#pragma unroll
-  for (int i = 0; i < T::MI; ++i) f.a[i] = read_frag<A_KS, T::BM, IMM_A>(ring, ring_lds, A_KS ? fo.a[i] : fo.a[i] ^ (KK << 5));
-#pragma unroll
-  for (int i = 0; i < T::NI; ++i) f.b[i] = read_frag<B_KS, T::BN, IMM_B>(ring, ring_lds, B_KS ? fo.b[i] : fo.b[i] ^ (KK << 5));
+  load_frags_seq<T, A_KS, B_KS, FRA, FRB, OFF_A, OFF_B, KK>(f, fa, std::make_integer_sequence<int, T::MI>{}, std::make_integer_sequence<int, T::NI>{});
 }
 // Wait until this wave's LDS reads have delivered, with the fragments as operands of the wait: the registers a
 // transposing read (an assembly statement, see read_frag) is filling stay reserved until here on every path --
@@ -371,8 +391,9 @@ __device__ __forceinline__ void mma(const Frags<T>& f, f32x16 (&acc)[T::MI][T::N
 // outstanding (about 128 lines, whatever is in flight in the rings): 64-byte row pieces (BK = 32) give about
 // 30 bytes per clock and CU on L2 hits, 128-byte pieces (BK = 64) about 60; the rings only have to keep that
 // window full, which a ring that drains at every slab (SA = SB = 2) does not.
-template <class T, bool A_KS, bool B_KS, bool A_GATHER = false, bool B_GATHER = false>
+template <class T, bool A_KS, bool B_KS, bool A_GATHER = false, bool B_GATHER = false, int FRB = 32>
 struct MainLoop {
+  static constexpr int FRA = 32;                       // tile rows between the wave's fragments, A side and B side
   typedef Dma<A_KS, T::BM, T::BK, T::kWaves, A_GATHER> DmaA;
   typedef Dma<B_KS, T::BN, T::BK, T::kWaves, B_GATHER> DmaB;
   static constexpr int NA = DmaA::N, NB = DmaB::N;     // loads per thread per slab and side
@@ -386,7 +407,7 @@ struct MainLoop {
 
   DmaA da;
   DmaB db;
-  FragOffsets<T> fo;
+  FragAddrs<T, A_KS, B_KS> fa;
   Frags<T> f0, f1;                                     // even / odd reduction steps
   char* lds;
   uint32_t lds32;                                      // the ring's start as an LDS address
@@ -419,7 +440,7 @@ struct MainLoop {
     if constexpr (KK + 1 < STEPS) {
       settle<T>((KK & 1) ? f1 : f0);
       __builtin_amdgcn_sched_barrier(0);
-      load_frags<T, A_KS, B_KS, SGA * T::kABytes, SGB * T::kBBytes, KK + 1>((KK & 1) ? f0 : f1, lds, lds32, fo);
+      load_frags<T, A_KS, B_KS, FRA, FRB, SGA * T::kABytes, SGB * T::kBBytes, KK + 1>((KK & 1) ? f0 : f1, fa);
       __builtin_amdgcn_sched_barrier(0);
       mma<T, 0, T::MI * T::NI>((KK & 1) ? f1 : f0, acc);
       __builtin_amdgcn_sched_barrier(0);
@@ -441,8 +462,15 @@ struct MainLoop {
     if (kt + 1 < nslabs) wait_loads_in_flight<(SA - 2) * NA + (SB - 2) * NB, kStep>(loads_beyond(kt));   // slab kt+1 has landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    // Products that read an operand transposed start with the last step's MFMAs (their LDS reads and the refill then
+    // issue under those MFMAs); the others first fetch and refill (measured: 1-3 % either way).
+    constexpr bool MMA_FIRST = A_KS || B_KS;
+    if constexpr (ACTIVE && MMA_FIRST) {
+      mma<T, 0, ALL>(f1, acc);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if constexpr (ACTIVE) {
-      if (kt + 1 < nslabs) load_frags<T, A_KS, B_KS, NXA * T::kABytes, NXB * T::kBBytes, 0>(f0, lds, lds32, fo);
+      if (kt + 1 < nslabs) load_frags<T, A_KS, B_KS, FRA, FRB, NXA * T::kABytes, NXB * T::kBBytes, 0>(f0, fa);
       __builtin_amdgcn_sched_barrier(0);
     }
     if constexpr (SB <= SA) {                          // the side whose slab is needed sooner goes first
@@ -452,9 +480,72 @@ struct MainLoop {
       if (kt + SA < nslabs) issue_a(kt + SA, SGA);
       if (kt + SB < nslabs) issue_b(kt + SB, SGB);
     }
-    if constexpr (ACTIVE) {
+    if constexpr (ACTIVE && !MMA_FIRST) {
       __builtin_amdgcn_sched_barrier(0);
       mma<T, 0, ALL>(f1, acc);
+    }
+  }
+
+  // The same for a wave with rows, when every slab the body touches is a full one that exists (slabs kt + 1, kt + SA and
+  // kt + SB below nfull): nothing branches, and the refill and the first LDS reads of the next slab are spread between
+  // the MFMAs of the last step, one group per MFMA -- they issue while the matrix pipe is busy with the MFMA before
+  // them instead of holding it up after the barrier.
+  template <int STG>
+  __device__ __forceinline__ void slab_interior(int kt, f32x16 (&acc)[T::MI][T::NI]) {
+    constexpr int SGA = STG % SA, SGB = STG % SB, NXA = (STG + 1) % SA, NXB = (STG + 1) % SB;
+    constexpr int ALL = T::MI * T::NI;
+    constexpr int LOADS = NA + NB;
+    constexpr int GAPS = ALL - 1;                      // the first gap takes the LDS reads, the others the loads
+    constexpr int PER = (LOADS + GAPS - 1) / GAPS;
+    static_assert(GAPS >= 1, "a wave has at least two MFMA tiles");
+    steps<SGA, SGB, 0>(acc);
+    settle<T>(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<(SA - 2) * NA + (SB - 2) * NB>();       // slab kt+1 has landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    mma_one<0>(acc);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags<T, A_KS, B_KS, FRA, FRB, NXA * T::kABytes, NXB * T::kBBytes, 0>(f0, fa);
+    __builtin_amdgcn_sched_barrier(0);
+    interior_gaps<SGA, SGB, 1, PER>(kt, acc);
+  }
+  // MFMA number M of the last step (operands in f1)
+  template <int M>
+  __device__ __forceinline__ void mma_one(f32x16 (&acc)[T::MI][T::NI]) { mma<T, M, M + 1>(f1, acc); }
+  // load number J of the refill: the side whose slab is needed sooner comes first
+  template <int SGA, int SGB, int J>
+  __device__ __forceinline__ void refill_one(int kt) {
+    constexpr bool B_FIRST = SB <= SA;
+    constexpr int N1 = B_FIRST ? NB : NA;
+    if constexpr (J < N1) {
+      if constexpr (B_FIRST) db.issue_one(J, kt + SB, buf_b(SGB), wave); else da.issue_one(J, kt + SA, buf_a(SGA), wave);
+      if constexpr (J == N1 - 1) { if constexpr (B_FIRST) db.fetch_rows(kt + SB + 1); else da.fetch_rows(kt + SA + 1); }
+    } else if constexpr (J < NA + NB) {
+      if constexpr (B_FIRST) da.issue_one(J - N1, kt + SA, buf_a(SGA), wave); else db.issue_one(J - N1, kt + SB, buf_b(SGB), wave);
+      if constexpr (J == NA + NB - 1) { if constexpr (B_FIRST) da.fetch_rows(kt + SA + 1); else db.fetch_rows(kt + SB + 1); }
+    }
+  }
+  template <int SGA, int SGB, int J, int JEND>
+  __device__ __forceinline__ void refill_range(int kt) {
+    if constexpr (J < JEND) { refill_one<SGA, SGB, J>(kt); refill_range<SGA, SGB, J + 1, JEND>(kt); }
+  }
+  template <int SGA, int SGB, int M, int PER>
+  __device__ __forceinline__ void interior_gaps(int kt, f32x16 (&acc)[T::MI][T::NI]) {
+    if constexpr (M < T::MI * T::NI) {
+      mma_one<M>(acc);
+      __builtin_amdgcn_sched_barrier(0);
+      refill_range<SGA, SGB, (M - 1) * PER, M * PER>(kt);
+      __builtin_amdgcn_sched_barrier(0);
+      interior_gaps<SGA, SGB, M + 1, PER>(kt, acc);
+    }
+  }
+  template <int STG>
+  __device__ __forceinline__ void interior_trip(int& kt, f32x16 (&acc)[T::MI][T::NI]) {
+    if constexpr (STG < U) {
+      slab_interior<STG>(kt, acc);
+      ++kt;
+      interior_trip<STG + 1>(kt, acc);
     }
   }
 
@@ -471,8 +562,14 @@ struct MainLoop {
 
   template <bool ACTIVE>
   __device__ __forceinline__ void stream(f32x16 (&acc)[T::MI][T::NI]) {
-    if constexpr (ACTIVE) load_frags<T, A_KS, B_KS, 0, 0, 0>(f0, lds, lds32, fo);
+    if constexpr (ACTIVE) load_frags<T, A_KS, B_KS, FRA, FRB, 0, 0, 0>(f0, fa);
     int kt = 0;
+    if constexpr (ACTIVE) {
+#pragma nounroll
+      while (kt + U + (SA > SB ? SA : SB) <= nfull) {  // trips that only touch full slabs: the branch-free bodies
+        interior_trip<0>(kt, acc);
+      }
+    }
 #pragma nounroll
     while (kt + U <= nslabs) {                         // U slabs per trip: buffers are compile-time
       run_from<0, ACTIVE>(kt, acc);
@@ -490,10 +587,19 @@ struct MainLoop {
     lds32 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)lds_));
     nfull = K > 0 ? K / T::BK : 0;
     nslabs = K > 0 ? (K + T::BK - 1) / T::BK : 0;
+    typedef FragAddrs<T, A_KS, B_KS> FA;
 #pragma unroll
-    for (int i = 0; i < T::MI; ++i) fo.a[i] = frag_off<A_KS, T::BM, T::BK>(a_row[i], 0, lane);
+    for (int i = 0; i < FA::NA; ++i) {                 // k-strided: fragment i at step 0; k-contiguous: fragment 0 at step i
+      if constexpr (A_KS) fa.a[i] = lds32 + frag_off<true, T::BM, T::BK>(a_row[i], 0, lane);
+      else fa.a[i] = lds32 + frag_off<false, T::BM, T::BK>(a_row[0], i, lane);
+      if constexpr (FA::A_FAR) fa.a_far[i] = fa.a[i] + 65536;
+    }
 #pragma unroll
-    for (int i = 0; i < T::NI; ++i) fo.b[i] = T::kBBase + frag_off<B_KS, T::BN, T::BK>(b_row[i], 0, lane);
+    for (int i = 0; i < FA::NB; ++i) {
+      if constexpr (B_KS) fa.b[i] = lds32 + T::kBBase + frag_off<true, T::BN, T::BK>(b_row[i], 0, lane);
+      else fa.b[i] = lds32 + T::kBBase + frag_off<false, T::BN, T::BK>(b_row[0], i, lane);
+      if constexpr (FA::B_FAR) fa.b_far[i] = fa.b[i] + 65536;
+    }
   }
   // point the loads at the operands of a segment and fill both rings, slab by slab (A before B), as far as they go.
   // The rings must be idle.
@@ -797,7 +903,8 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     opB.half[0] = p.w0 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.half[1] = p.w1 + e * p.w_expert_stride + static_cast<long>(n0) * p.ldw;
     opB.valid[0] = opB.valid[1] = ncols;
-    { MainLoop<T, false, false, FUSED, false> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
+    static_assert(HI == 1, "the wave's gate fragment and its up fragment: two fragments BN/2 tile rows apart");
+    { MainLoop<T, false, false, FUSED, false, HN> ml; ml.run(opsA, opsB, 1, p.K, lds, p.zeros, a_row, b_row, mi_n > 0, acc); }
     // strip columns: [0, HW) gate, [WN/2 + 0, ...) up -- both halves hold the same output columns
     float* strip = reinterpret_cast<float*>(lds + T::kStripBase + wave * Strip<T>::kBytes);
     const int el = not_before_here(lane);             // this lane, for the epilogue
@@ -1436,7 +1543,7 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
 template <int WHICH, bool GATHER = false>
 static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
   // [dW_gate; dW_up] with short reductions is faster with TileBig's paired column tiles
-  if (WHICH == 0 || (WHICH == 1 && p.P >= 1024L * p.E)) {
+  if (WHICH == 0 || (WHICH == 1 && p.P >= 1536L * p.E)) {
     if constexpr (WHICH < 2) launch_wgrad_t<WHICH, TileBigW16, GATHER>(p, s);
   } else {
     launch_wgrad_t<WHICH, TileBig, GATHER>(p, s);

@@ -144,58 +144,77 @@ template <> struct Piece<MOE_F32> {
 };
 
 // ---- combine forward: y[t] = sum_j w[t,j] * yp[row(t,j)] ------------------------------------
-// One thread per 16-byte piece of y.  The slot indices and weights of the token are fetched first, then
-// the source pieces of up to eight slots are all in flight together before the fp32 sum, which runs in
-// slot order (the same order on every run).  KB = slots per batch.
-template <int DT, int KB>
+// One thread per PPT 16-byte pieces of y (a workgroup covers PPT x 256 consecutive pieces, piece u of a thread 256
+// pieces after piece u-1, so every access of a wave is 1 KiB contiguous).  The slot indices and weights of the tokens
+// are fetched first, then KB slots x PPT pieces are all in flight together before the fp32 sums, which run in slot
+// order (the same order on every run).
+template <int DT, int KB, int PPT>
 __global__ __launch_bounds__(kMoverThreads) void combine_fwd_kernel(
     const uint4* __restrict__ yp, int T, int k, int n16, const float* __restrict__ topk_w,
     const int32_t* __restrict__ row_of_pair, uint4* __restrict__ y) {
   constexpr int N = Piece<DT>::N;
-  const size_t piece = static_cast<size_t>(blockIdx.x) * kMoverThreads + threadIdx.x;
   const size_t total = static_cast<size_t>(T) * n16;
-  if (piece >= total) return;
-  const int t = static_cast<int>(piece / n16);
-  const int c = static_cast<int>(piece % n16);
-  float acc[N];
-#pragma unroll
-  for (int i = 0; i < N; ++i) acc[i] = 0.0f;
-  const int32_t* rows = row_of_pair + static_cast<size_t>(t) * k;
-  const float* w = topk_w ? topk_w + static_cast<size_t>(t) * k : nullptr;
+  const size_t first = static_cast<size_t>(blockIdx.x) * (kMoverThreads * PPT) + threadIdx.x;
   const int last = T * k - 1;
+  float acc[PPT][N];
+  int t[PPT], c[PPT];
+#pragma unroll
+  for (int u = 0; u < PPT; ++u) {
+    const size_t piece = min(first + static_cast<size_t>(u) * kMoverThreads, total - 1);   // pieces past the end repeat the last one (not stored)
+    t[u] = static_cast<int>(piece / n16);
+    c[u] = static_cast<int>(piece % n16);
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[u][i] = 0.0f;
+  }
   for (int j = 0; j < k; j += KB) {
-    int r[KB];
-    float wj[KB];
+    int r[PPT][KB];
+    float wj[PPT][KB];
 #pragma unroll
-    for (int u = 0; u < KB; ++u) {                       // slots beyond k repeat the last one with weight 0
-      const int ju = min(j + u, k - 1);
-      r[u] = min(max(rows[ju], 0), last);
-      wj[u] = j + u < k ? (w ? w[ju] : 1.0f) : 0.0f;
-    }
-    uint4 v[KB];
+    for (int u = 0; u < PPT; ++u) {
+      const int32_t* rows = row_of_pair + static_cast<size_t>(t[u]) * k;
+      const float* w = topk_w ? topk_w + static_cast<size_t>(t[u]) * k : nullptr;
 #pragma unroll
-    for (int u = 0; u < KB; ++u) v[u] = load16_stream(yp + static_cast<size_t>(r[u]) * n16 + c);
-#pragma unroll
-    for (int u = 0; u < KB; ++u) {
-      if (j + u < k) {
-        float f[N];
-        Piece<DT>::unpack(v[u], f);
-#pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] = fmaf(wj[u], f[i], acc[i]);
+      for (int q = 0; q < KB; ++q) {                     // slots beyond k repeat the last one with weight 0
+        const int jq = min(j + q, k - 1);
+        r[u][q] = min(max(rows[jq], 0), last);
+        wj[u][q] = j + q < k ? (w ? w[jq] : 1.0f) : 0.0f;
       }
     }
+    uint4 v[PPT][KB];
+#pragma unroll
+    for (int u = 0; u < PPT; ++u)
+#pragma unroll
+      for (int q = 0; q < KB; ++q) v[u][q] = load16_stream(yp + static_cast<size_t>(r[u][q]) * n16 + c[u]);
+#pragma unroll
+    for (int u = 0; u < PPT; ++u)
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        if (j + q < k) {
+          float f[N];
+          Piece<DT>::unpack(v[u][q], f);
+#pragma unroll
+          for (int i = 0; i < N; ++i) acc[u][i] = fmaf(wj[u][q], f[i], acc[u][i]);
+        }
+      }
   }
-  store16_stream(y + piece, Piece<DT>::pack(acc));
+#pragma unroll
+  for (int u = 0; u < PPT; ++u) {
+    const size_t piece = first + static_cast<size_t>(u) * kMoverThreads;
+    if (piece < total) store16_stream(y + piece, Piece<DT>::pack(acc[u]));
+  }
 }
 
 // ---- combine backward: dyp[row] = w * dy[t];  dw[t,j] = <dy[t], yp[row]> --------------------
-// One wave per token; the wave walks the row in 64-piece strides, slot by slot.
-template <int DT>
+// One wave per token.  The token's row of dy is read once per 256-piece stretch and kept in registers; the matching
+// pieces of up to KB slots' yp rows are requested together, then each slot's dyp pieces are written and its dot
+// product accumulated; the KB dot products are reduced across the wave at the end, all in a fixed order.
+template <int DT, int KB>
 __global__ __launch_bounds__(kMoverThreads) void combine_bwd_kernel(
     const uint4* __restrict__ dy, const uint4* __restrict__ yp, int T, int k, int n16,
     const float* __restrict__ topk_w, const int32_t* __restrict__ row_of_pair,
     uint4* __restrict__ dyp, float* __restrict__ dw) {
   constexpr int N = Piece<DT>::N;
+  constexpr int PL = 4;                                  // pieces per lane and stretch
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * (kMoverThreads / 64) + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -207,34 +226,53 @@ __global__ __launch_bounds__(kMoverThreads) void combine_bwd_kernel(
     my_w = topk_w[static_cast<size_t>(t) * k + lane];
   }
   float my_dot = 0.0f;
-  for (int j = 0; j < k; ++j) {
-    const int row = __shfl(my_row, j, 64);
-    const float wj = __shfl(my_w, j, 64);
-    const uint4* src = yp + static_cast<size_t>(row) * n16;
-    uint4* dst = dyp + static_cast<size_t>(row) * n16;
-    float dot = 0.0f;
-    for (int c0 = 0; c0 < n16; c0 += 256) {
-      uint4 a[4], b[4];
+  for (int j0 = 0; j0 < k; j0 += KB) {
+    int row[KB];
+    float wj[KB], dot[KB];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        int c = c0 + u * 64 + lane;
-        if (c < n16) { a[u] = dyr[c]; b[u] = load16_stream(src + c); }
+    for (int q = 0; q < KB; ++q) {                       // slots beyond k repeat the last one; nothing of theirs is stored
+      const int jq = min(j0 + q, k - 1);
+      row[q] = __shfl(my_row, jq, 64);
+      wj[q] = __shfl(my_w, jq, 64);
+      dot[q] = 0.0f;
+    }
+    for (int c0 = 0; c0 < n16; c0 += 64 * PL) {
+      uint4 a[PL], b[KB][PL];
+#pragma unroll
+      for (int u = 0; u < PL; ++u) {
+        const int c = min(c0 + u * 64 + lane, n16 - 1);
+        a[u] = dyr[c];
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        int c = c0 + u * 64 + lane;
-        if (c < n16) {
-          float fa[N], fb[N], fo[N];
-          Piece<DT>::unpack(a[u], fa);
-          Piece<DT>::unpack(b[u], fb);
+      for (int q = 0; q < KB; ++q)
 #pragma unroll
-          for (int i = 0; i < N; ++i) { dot = fmaf(fa[i], fb[i], dot); fo[i] = wj * fa[i]; }
-          store16_stream(dst + c, Piece<DT>::pack(fo));
+        for (int u = 0; u < PL; ++u) {
+          const int c = min(c0 + u * 64 + lane, n16 - 1);
+          b[q][u] = load16_stream(yp + static_cast<size_t>(row[q]) * n16 + c);
+        }
+#pragma unroll
+      for (int q = 0; q < KB; ++q) {
+        if (j0 + q < k) {
+#pragma unroll
+          for (int u = 0; u < PL; ++u) {
+            const int c = c0 + u * 64 + lane;
+            if (c < n16) {
+              float fa[N], fb[N], fo[N];
+              Piece<DT>::unpack(a[u], fa);
+              Piece<DT>::unpack(b[q][u], fb);
+#pragma unroll
+              for (int i = 0; i < N; ++i) { dot[q] = fmaf(fa[i], fb[i], dot[q]); fo[i] = wj[q] * fa[i]; }
+              store16_stream(dyp + static_cast<size_t>(row[q]) * n16 + c, Piece<DT>::pack(fo));
+            }
+          }
         }
       }
     }
-    dot = wave_sum(dot);
-    if (lane == j) my_dot = dot;
+#pragma unroll
+    for (int q = 0; q < KB; ++q) {
+      const float d = wave_sum(dot[q]);
+      if (lane == j0 + q) my_dot = d;
+    }
   }
   if (lane < k) dw[static_cast<size_t>(t) * k + lane] = my_dot;
 }
@@ -305,17 +343,18 @@ extern "C" int32_t moe_unpermute_combine_fwd(const void* yp, int dtype, int T, i
   begin_call("moe_unpermute_combine_fwd", s);
   const int n16 = d * elem_size(dtype) / 16;
   const size_t total = static_cast<size_t>(T) * n16;
-  const unsigned blocks = static_cast<unsigned>((total + kMoverThreads - 1) / kMoverThreads);
-  // eight slots in flight per thread when the token has that many, else four, two or one
-#define MOE_COMBINE_FWD(DT, KB) \
-  MOE_LAUNCH("combine_fwd", (combine_fwd_kernel<DT, KB>), dim3(blocks), dim3(kMoverThreads), 0, s, \
-             static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair, static_cast<uint4*>(y))
+  // KB slots of a token x PPT pieces in flight per thread.  Measured: with one slot per token (rows delivered by an
+  // expert-parallel dispatch) more pieces per thread are slower (0.56 of the HBM peak with eight against 0.62 with one:
+  // the launch is 27 us long and fewer, fatter threads fill the chip later), so PPT stays 1.
+#define MOE_COMBINE_FWD(DT, KB, PPT) \
+  MOE_LAUNCH("combine_fwd", (combine_fwd_kernel<DT, KB, PPT>), dim3(static_cast<unsigned>((total + kMoverThreads * PPT - 1) / (kMoverThreads * PPT))), \
+             dim3(kMoverThreads), 0, s, static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair, static_cast<uint4*>(y))
   if (dtype == MOE_BF16) {
-    if (k >= 8) MOE_COMBINE_FWD(MOE_BF16, 8); else if (k >= 3) MOE_COMBINE_FWD(MOE_BF16, 4);
-    else if (k == 2) MOE_COMBINE_FWD(MOE_BF16, 2); else MOE_COMBINE_FWD(MOE_BF16, 1);
+    if (k >= 8) MOE_COMBINE_FWD(MOE_BF16, 8, 1); else if (k >= 3) MOE_COMBINE_FWD(MOE_BF16, 4, 1);
+    else if (k == 2) MOE_COMBINE_FWD(MOE_BF16, 2, 1); else MOE_COMBINE_FWD(MOE_BF16, 1, 1);
   } else {
-    if (k >= 8) MOE_COMBINE_FWD(MOE_F32, 8); else if (k >= 3) MOE_COMBINE_FWD(MOE_F32, 4);
-    else if (k == 2) MOE_COMBINE_FWD(MOE_F32, 2); else MOE_COMBINE_FWD(MOE_F32, 1);
+    if (k >= 8) MOE_COMBINE_FWD(MOE_F32, 8, 1); else if (k >= 3) MOE_COMBINE_FWD(MOE_F32, 4, 1);
+    else if (k == 2) MOE_COMBINE_FWD(MOE_F32, 2, 1); else MOE_COMBINE_FWD(MOE_F32, 1, 1);
   }
 #undef MOE_COMBINE_FWD
   return end_call();
@@ -332,13 +371,14 @@ extern "C" int32_t moe_unpermute_combine_bwd(const void* dy, const void* yp, int
   begin_call("moe_unpermute_combine_bwd", s);
   const int n16 = d * elem_size(dtype) / 16;
   const unsigned blocks = static_cast<unsigned>(ceil_div(T, kMoverThreads / 64));
-  if (dtype == MOE_BF16)
-    MOE_LAUNCH("combine_bwd", combine_bwd_kernel<MOE_BF16>, dim3(blocks), dim3(kMoverThreads), 0, s,
-                       static_cast<const uint4*>(dy), static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair,
-                       static_cast<uint4*>(dyp), dw);
-  else
-    MOE_LAUNCH("combine_bwd", combine_bwd_kernel<MOE_F32>, dim3(blocks), dim3(kMoverThreads), 0, s,
-                       static_cast<const uint4*>(dy), static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair,
-                       static_cast<uint4*>(dyp), dw);
+#define MOE_COMBINE_BWD(DT, KB) \
+  MOE_LAUNCH("combine_bwd", (combine_bwd_kernel<DT, KB>), dim3(blocks), dim3(kMoverThreads), 0, s, static_cast<const uint4*>(dy), \
+             static_cast<const uint4*>(yp), T, k, n16, topk_w, row_of_pair, static_cast<uint4*>(dyp), dw)
+  if (dtype == MOE_BF16) {
+    if (k >= 4) MOE_COMBINE_BWD(MOE_BF16, 4); else if (k >= 2) MOE_COMBINE_BWD(MOE_BF16, 2); else MOE_COMBINE_BWD(MOE_BF16, 1);
+  } else {
+    if (k >= 4) MOE_COMBINE_BWD(MOE_F32, 4); else if (k >= 2) MOE_COMBINE_BWD(MOE_F32, 2); else MOE_COMBINE_BWD(MOE_F32, 1);
+  }
+#undef MOE_COMBINE_BWD
   return end_call();
 }

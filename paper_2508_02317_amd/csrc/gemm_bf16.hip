@@ -1228,6 +1228,9 @@ struct WgradArgs {
   float* partial;                              // [max_slots][M][N]
   const bf16_t* zeros;     // at least 16 zero bytes
   const int32_t* row_token;    // GATHER kernels: [P + padding], token of each expert-ordered row
+  // a side job of the reduction launch that follows dW_down in the gathered backward (null: none): the partial dot
+  // products of the combine-weight gradient, one per (column slot, row), are added in slot order and scattered to [T, k]
+  const float* dw_partial; int dw_slots; const int32_t* pair_of_row; float* dtopk_w;
 };
 
 // Column tiles one workgroup of a weight-gradient product takes in turn (see the kernel).  Measured in the layer
@@ -1371,6 +1374,13 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
 // (the split experts are taken in turn by the same blocks: with balanced routing there are none, and the launch
 // is a few hundred blocks that read one counter and leave)
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
+  if (p.dw_partial) {                                  // dtopk_w[pair_of_row[r]] = sum over the column slots, in slot order
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < p.P; r += gridDim.x * 256) {
+      float s = 0.0f;
+      for (int j = 0; j < p.dw_slots; ++j) s += p.dw_partial[static_cast<long>(j) * p.P + r];
+      p.dtopk_w[min(max(p.pair_of_row[r], 0), p.P - 1)] = s;
+    }
+  }
   const int n_split = p.items.count[1];
   const long mn = static_cast<long>(p.M) * p.N;
   for (int s = 0; s < n_split; ++s) {
@@ -1534,8 +1544,9 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   const unsigned grid = padded_grid(p.tiles_m * ceil_div(p.tiles_n, kWgradSpan<T, WHICH>) * (p.items.max_items + kXcds));
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T, GATHER>), dim3(grid),
              dim3(T::kThreads), T::kLdsAlloc, s, p);
-  const long rblocks = (static_cast<long>(p.M) * p.N + 2047) / 2048;
-  const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 1024L)));
+  // the reduction loops are grid-strided: a launch with nothing to reduce (balanced routing) should cost as little as a launch can
+  const long rblocks = std::max((static_cast<long>(p.M) * p.N + 2047) / 2048, p.dw_partial ? (static_cast<long>(p.P) + 255) / 256 : 1L);
+  const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 512L)));
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down_reduce" : WHICH == 1 ? "wgrad_gate_up_reduce" : "wgrad_router_reduce", wgrad_reduce_kernel, rgrid,
              dim3(256), 0, s, p);
 }
@@ -1654,16 +1665,6 @@ void ffn_bwd_bf16(const FfnBwdArgs& a) {
 // weight-gradient products never leave it.
 // ============================================================================================
 
-// dw[pair_of_row[r]] = sum over the column slots, in slot order, of the partial dot products of row r
-__global__ __launch_bounds__(256) void finish_dw_kernel(const float* __restrict__ partial, int slots, int P,
-                                                         const int32_t* __restrict__ pair_of_row, float* __restrict__ dw) {
-  const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= P) return;
-  float s = 0.0f;
-  for (int j = 0; j < slots; ++j) s += partial[static_cast<long>(j) * P + r];
-  dw[min(max(pair_of_row[r], 0), P - 1)] = s;
-}
-
 // column slots of the partial dot products: one per (column tile, wavefront column) of the dA product
 static int dw_slots(int f) { return ceil_div(f, TileBig::BN) * TileBig::WGN; }
 
@@ -1739,9 +1740,6 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
     p.row_token = row_token; p.row_w = row_w; p.act_w = act_w; p.dw_partial = dw_partial;
     launch_row<kDAct, true>(p, a.P, a.E, a.stream);
   }
-  if (a.P > 0)
-    MOE_LAUNCH("finish_dw", finish_dw_kernel, dim3(ceil_div(a.P, 256)), dim3(256), 0, a.stream, dw_partial, dw_slots(a.f), a.P,
-               a.pair_of_row, a.dtopk_w);
   launch_dx(dgu, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.dxp, a.stream);
   float* partial = reinterpret_cast<float*>(base + w.partial);
   {  // dWd[e] = dy[token]^T (w act)
@@ -1751,6 +1749,7 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
     p.E = a.E; p.P = a.P; p.items = items; p.partial = partial; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = static_cast<bf16_t*>(a.dw_down); p.out1 = p.out0; p.m_split = a.d;
     p.row_token = row_token;
+    p.dw_partial = dw_partial; p.dw_slots = dw_slots(a.f); p.pair_of_row = a.pair_of_row; p.dtopk_w = a.dtopk_w;   // rides in the reduction launch
     launch_wgrad<0, true>(p, a.stream);
   }
   {  // [dWg[e]; dWu[e]] = [dG | dU]^T x[token]

@@ -83,6 +83,41 @@ int32_t moe_route_topk(const float* logits, int T, int E, int k, int renorm,
                        int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
                        void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Expert forward with 8-bit operands (a widening beyond the paper, which says "mixed precision" and no more: App. A,
+ * Table 4 caption).  Format: OCP MXFP8 -- elements in OFP8 E4M3 (bias 7, largest magnitude 448, no infinities),
+ * one E8M0 scale 2^(s-127) per 32 consecutive elements of the REDUCTION dimension; an entry is scale * element.
+ *
+ * moe_mx8_quantise: src [rows, K] bf16 (device, row-major, contiguous) -> codes [rows, K] uint8 and scales, both device.
+ *   Per block: s = max(biased float32 exponent of max|v| - 8, 0) (= floor(log2 max|v|) - 8 + 127 clamped at 0; an
+ *   all-zero block gets 0), element = v / 2^(s-127) rounded to nearest even in E4M3 and saturated at +-448.  The
+ *   arithmetic is exact up to that one rounding.  Scales are packed four to a 32-bit word, laid out
+ *   [K/128][rows]: byte j (little endian) of word (g, row) belongs to elements 128 g + 32 j .. + 31 of the row.
+ *   K must be a multiple of 128.  NaN and infinite inputs are not supported (result unspecified, no fault).
+ *
+ * moe_grouped_gemm_swiglu_fwd_mx8 (SwiGLU expert of Sec. 3.2.5 on the stacked weights of App. B.6):
+ *   G = x Wg[e]^T, U = x Wu[e]^T with fp32 accumulation of the exact products of the scaled elements;
+ *   act = silu(G) * U in fp32, quantised along f as above straight from fp32 (never rounded to bf16);
+ *   yp = act Wd[e]^T, fp32 accumulation, rounded to bf16 once.
+ *   xq, xs: codes [T, d] and scales [d/128][T] of the layer input, read by token through pair_of_row [P]
+ *     (P = T * k; row r is token pair_of_row[r] / k), or -- pair_of_row NULL -- codes [P, d], scales [d/128][P]
+ *     in expert order (T = P, k = 1).
+ *   wgq, wuq [E, f, d] codes with wgs, wus [d/128][E*f] scales; wdq [E, d, f] codes with wds [f/128][E*d] scales
+ *     (each weight quantised as one matrix of E*f, resp. E*d, rows).
+ *   offsets [E+1] as for moe_grouped_gemm_swiglu_fwd.
+ *   actq [P, f] codes out, acts [f/128][P] scales out (input format of the second product), yp [P, d] bf16 out.
+ *   d and f must be multiples of 128; T * d < 2^32 when rows are read by token.  ws, ws_bytes: device workspace of
+ *   at least moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(P, d, f, E).
+ * Errors as everywhere: INVALID_ARG / UNSUPPORTED / WORKSPACE mean nothing was launched.
+ */
+int32_t moe_mx8_quantise(const void* src, int64_t rows, int K, void* codes, void* scales, void* stream);
+size_t moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(int P, int d, int f, int E);
+int32_t moe_grouped_gemm_swiglu_fwd_mx8(const void* xq, const void* xs, int T, int k, const int32_t* pair_of_row,
+                                        const void* wgq, const void* wgs, const void* wuq, const void* wus,
+                                        const void* wdq, const void* wds, int P, int d, int f, int E,
+                                        const int32_t* offsets, void* actq, void* acts, void* yp, void* ws,
+                                        size_t ws_bytes, void* stream);
+
 /* moe_route_topk for callers that cannot allocate and have no workspace to pass: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without ws), same
  * kernels, same results bit for bit.  The per-workgroup histogram rows live in a static device array

@@ -196,6 +196,53 @@ extern "C" int32_t moe_grouped_gemm_swiglu_bwd_gather(const void* dy, const void
   return end_call();
 }
 
+// ---- 8-bit operands ----------------------------------------------------------------------------------
+extern "C" int32_t moe_mx8_quantise(const void* src, int64_t rows, int K, void* codes, void* scales, void* stream) {
+  MOE_REQUIRE(rows >= 0 && K > 0, MOE_ERR_INVALID_ARG, "mx8_quantise: need rows >= 0 and K > 0 (rows=%lld K=%d)", static_cast<long long>(rows), K);
+  MOE_REQUIRE(K % 128 == 0, MOE_ERR_UNSUPPORTED, "mx8_quantise: K=%d must be a multiple of 128 (four 32-element blocks per packed scale word)", K);
+  MOE_REQUIRE(rows * (K / 8) < (int64_t{1} << 39), MOE_ERR_UNSUPPORTED, "mx8_quantise: matrix too large");
+  if (rows == 0) return MOE_OK;
+  MOE_REQUIRE(src && codes && scales, MOE_ERR_INVALID_ARG, "mx8_quantise: null pointer");
+  MOE_REQUIRE(aligned16(src) && aligned16(codes) && aligned16(scales), MOE_ERR_INVALID_ARG, "mx8_quantise: tensors must be 16-byte aligned");
+  Mx8QuantArgs a{src, static_cast<long>(rows), K, codes, scales, static_cast<hipStream_t>(stream)};
+  begin_call("moe_mx8_quantise", static_cast<hipStream_t>(stream));
+  mx8_quantise(a);
+  return end_call();
+}
+
+static int32_t check_mx8_dims(int P, int d, int f, int E, int T, int k, bool gathered) {
+  if (int32_t rc = check_ffn_dims("ffn_fwd_mx8", MOE_BF16, P, d, f, E)) return rc;
+  MOE_REQUIRE(d % 128 == 0 && f % 128 == 0, MOE_ERR_UNSUPPORTED, "ffn_fwd_mx8: d=%d and f=%d must be multiples of 128", d, f);
+  if (gathered) {
+    MOE_REQUIRE(T >= 0 && k >= 1 && static_cast<int64_t>(T) * k == P, MOE_ERR_INVALID_ARG, "ffn_fwd_mx8: P=%d is not T*k (T=%d k=%d)", P, T, k);
+    MOE_REQUIRE(static_cast<int64_t>(T) * d < (int64_t{1} << 32), MOE_ERR_UNSUPPORTED, "ffn_fwd_mx8: T*d must fit 32 bits (rows are addressed with 32-bit byte offsets)");
+  }
+  return MOE_OK;
+}
+
+extern "C" size_t moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(int P, int d, int f, int E) {
+  if (P < 0 || d <= 0 || f <= 0 || E <= 0) return 0;
+  return ffn_fwd_mx8_ws_bytes(P, d, f, E);
+}
+
+extern "C" int32_t moe_grouped_gemm_swiglu_fwd_mx8(const void* xq, const void* xs, int T, int k, const int32_t* pair_of_row,
+                                                   const void* wgq, const void* wgs, const void* wuq, const void* wus,
+                                                   const void* wdq, const void* wds, int P, int d, int f, int E,
+                                                   const int32_t* offsets, void* actq, void* acts, void* yp, void* ws,
+                                                   size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_mx8_dims(P, d, f, E, T, k, pair_of_row != nullptr)) return rc;
+  if (P == 0) return MOE_OK;
+  MOE_REQUIRE(xq && xs && wgq && wgs && wuq && wus && wdq && wds && offsets && actq && acts && yp, MOE_ERR_INVALID_ARG, "ffn_fwd_mx8: null pointer");
+  MOE_REQUIRE(aligned16(xq) && aligned16(xs) && aligned16(wgq) && aligned16(wgs) && aligned16(wuq) && aligned16(wus) && aligned16(wdq) &&
+              aligned16(wds) && aligned16(actq) && aligned16(acts) && aligned16(yp), MOE_ERR_INVALID_ARG, "ffn_fwd_mx8: tensors must be 16-byte aligned");
+  const size_t need = moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(P, d, f, E);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_fwd_mx8: workspace null, misaligned or smaller than %zu bytes", need);
+  FfnFwdMx8Args a{xq, xs, T, k, pair_of_row, wgq, wgs, wuq, wus, wdq, wds, P, d, f, E, offsets, actq, acts, yp, ws, static_cast<hipStream_t>(stream)};
+  begin_call("moe_grouped_gemm_swiglu_fwd_mx8", static_cast<hipStream_t>(stream));
+  ffn_fwd_mx8(a);
+  return end_call();
+}
+
 // ---- router linear -----------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) {
   const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;

@@ -1876,4 +1876,9 @@ void router_bwd_bf16(const RouterBwdArgs& a) {
   }
 }
 
+// ============================================================================================
+// Forward products with 8-bit block-scaled operands (same tiles, loaders and staging strips)
+// ============================================================================================
+#include "gemm_mx8.inc"
+
 }  // namespace moe

@@ -124,6 +124,27 @@ struct FfnBwdGatherArgs {
   void* ws;
   hipStream_t stream;
 };
+// 8-bit (MXFP8) operands: quantiser and forward products
+struct Mx8QuantArgs {
+  const void* src;                    // [rows, K] bf16
+  long rows; int K;
+  void *codes, *scales;               // [rows, K] E4M3 codes; [K/128][rows] packed scale words
+  hipStream_t stream;
+};
+struct FfnFwdMx8Args {
+  const void *xq, *xs;                // [T, d] codes and [d/128][T] scales (pair_of_row given) or [P, d] and [d/128][P]
+  int T, k;
+  const int32_t* pair_of_row;         // [P] or null
+  const void *wgq, *wgs, *wuq, *wus, *wdq, *wds;
+  int P, d, f, E;
+  const int32_t* offsets;
+  void *actq, *acts, *yp;
+  void* ws;
+  hipStream_t stream;
+};
+void mx8_quantise(const Mx8QuantArgs& a);
+size_t ffn_fwd_mx8_ws_bytes(int P, int d, int f, int E);
+void ffn_fwd_mx8(const FfnFwdMx8Args& a);
 size_t ffn_fwd_gather_ws_bytes_bf16(int P, int d, int f, int E);
 size_t ffn_bwd_gather_ws_bytes_bf16(int P, int d, int f, int E, int have_saved);
 void ffn_fwd_gather_bf16(const FfnFwdGatherArgs& a);

@@ -30,6 +30,7 @@ EXPORTS = [
     "moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes", "moe_grouped_gemm_swiglu_bwd_gather",
     "moe_unpermute_combine_fwd", "moe_unpermute_combine_bwd",
     "moe_router_logits_workspace_bytes", "moe_router_logits", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
+    "moe_mx8_quantise", "moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes", "moe_grouped_gemm_swiglu_fwd_mx8",
     "moe_set_launch_hook",
 ]
 
@@ -101,6 +102,12 @@ def _load():
     lib.moe_router_bwd_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.moe_router_bwd.restype = ctypes.c_int32
     lib.moe_router_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.moe_mx8_quantise.restype = ctypes.c_int32
+    lib.moe_mx8_quantise.argtypes = [vp, ctypes.c_int64, i32, vp, vp, vp]
+    lib.moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes.restype = sz
+    lib.moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.moe_grouped_gemm_swiglu_fwd_mx8.restype = ctypes.c_int32
+    lib.moe_grouped_gemm_swiglu_fwd_mx8.argtypes = [vp, vp, i32, i32, vp] + [vp] * 6 + [i32] * 4 + [vp] * 5 + [sz, vp]
     lib.moe_set_launch_hook.restype = ctypes.c_int32
     lib.moe_set_launch_hook.argtypes = [LAUNCH_HOOK, vp]
     return lib
@@ -288,6 +295,48 @@ def moe_grouped_gemm_swiglu_fwd_gather(x, k, pair_of_row, w_gate, w_up, w_down, 
                                                   code, P, d, f, E, _ptr(offsets), _ptr(g), _ptr(u), _ptr(act), _ptr(yp),
                                                   _ptr(ws), nbytes, _stream()))
     return act, yp, g, u
+
+
+def moe_mx8_quantise(src, out=None):
+    """bf16 [..., K] -> (E4M3 codes uint8 [..., K], packed scale words int32 [K/128, rows]) with rows = the product of the
+    leading dimensions; byte j of word (g, row) is the power-of-two scale code of elements 128 g + 32 j .. + 31 of the row."""
+    _need(src, torch.bfloat16, "src")
+    K = src.shape[-1]
+    rows = src.numel() // K if K else 0
+    if out is None:
+        out = (torch.empty(src.shape, dtype=torch.uint8, device=src.device),
+               torch.empty((max(K // 128, 0), rows), dtype=torch.int32, device=src.device))
+    codes, scales = out
+    _check(lib.moe_mx8_quantise(_ptr(src), rows, K, _ptr(codes), _ptr(scales), _stream()))
+    return codes, scales
+
+
+def moe_grouped_gemm_swiglu_fwd_mx8(xq, xs, wgq, wgs, wuq, wus, wdq, wds, offsets, pair_of_row=None, k=1, out=None, ws=None):
+    """Expert forward with 8-bit block-scaled operands (from moe_mx8_quantise).  xq [T, d] codes read by token through
+    pair_of_row [P] (P = T * k), or [P, d] in expert order when pair_of_row is None.
+    -> act codes uint8 [P, f], act scale words int32 [f/128, P], yp bf16 [P, d]."""
+    _need(xq, torch.uint8, "xq"); _need(xs, torch.int32, "xs"); _need(offsets, torch.int32, "offsets")
+    for name, w in (("wgq", wgq), ("wuq", wuq), ("wdq", wdq)):
+        _need(w, torch.uint8, name)
+    for name, w in (("wgs", wgs), ("wus", wus), ("wds", wds)):
+        _need(w, torch.int32, name)
+    T, d = xq.shape
+    E, f, _ = wgq.shape
+    if pair_of_row is not None:
+        _need(pair_of_row, torch.int32, "pair_of_row")
+        P = T * k
+    else:
+        P, k = T, 1
+    dev = xq.device
+    if out is None:
+        out = (torch.empty((P, f), dtype=torch.uint8, device=dev), torch.empty((max(f // 128, 0), P), dtype=torch.int32, device=dev),
+               torch.empty((P, d), dtype=torch.bfloat16, device=dev))
+    actq, acts, yp = out
+    ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(P, d, f, E), ws, dev)
+    _check(lib.moe_grouped_gemm_swiglu_fwd_mx8(_ptr(xq), _ptr(xs), T, k, _ptr(pair_of_row), _ptr(wgq), _ptr(wgs), _ptr(wuq), _ptr(wus),
+                                               _ptr(wdq), _ptr(wds), P, d, f, E, _ptr(offsets), _ptr(actq), _ptr(acts), _ptr(yp),
+                                               _ptr(ws), nbytes, _stream()))
+    return actq, acts, yp
 
 
 def moe_grouped_gemm_swiglu_bwd_gather(dy, x, topk_w, pair_of_row, g_save, u_save, w_gate, w_up, w_down, offsets,

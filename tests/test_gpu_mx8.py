@@ -1,0 +1,142 @@
+"""GPU parity of the 8-bit (MXFP8) forward products against oracle/moe_fp8.py, through the C ABI.
+
+The quantiser is exact arithmetic followed by one rounding, so its codes and scales are compared bit for bit.
+The products are compared on operands quantised by the ORACLE (both sides consume identical codes and scales):
+the activation codes may differ from the oracle's where the kernel's fp32 activation and the oracle's fp64 one
+fall on different sides of a rounding boundary, so they are compared as values -- never more than one E4M3 step
+of their block apart, and identical for all but a small fraction -- and Yp within the bf16 tolerance."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import moe_fp8 as F
+from oracle import moe_oracle as O
+from paper_2508_02317_amd.inputs import CONFIGS, make_inputs, scaled
+from tests.util import TOL, rel_err, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True, file=sys.stderr)
+
+
+def pack_scales(s):
+    """oracle scale codes [rows, K/32] uint8 -> the library's words [K/128, rows] int32 (byte j = block 4 g + j)."""
+    rows, nb = s.shape
+    words = np.ascontiguousarray(s.reshape(rows, nb // 4, 4)).view("<u4")[..., 0]
+    return np.ascontiguousarray(words.T).view(np.int32)
+
+
+def unpack_scales(w):
+    """inverse of pack_scales: int32 [K/128, rows] -> uint8 [rows, K/32]"""
+    g, rows = w.shape
+    return np.ascontiguousarray(np.ascontiguousarray(w).view(np.uint32).T).view(np.uint8).reshape(rows, g * 4)
+
+
+def test_pack_helpers_round_trip():
+    s = np.arange(6 * 8, dtype=np.uint8).reshape(6, 8)
+    assert np.array_equal(unpack_scales(pack_scales(s)), s)
+    assert pack_scales(s)[1, 2] == int.from_bytes(bytes(s[2, 4:8]), "little")
+
+
+@pytest.mark.parametrize("rows,K,seed", [(1, 128, 0), (77, 256, 1), (300, 384, 2), (1000, 2048, 3)])
+def test_quantiser_bit_exact(rows, K, seed):
+    import torch
+    from paper_2508_02317_amd import libmoe as L
+    rng = np.random.default_rng(seed)
+    V = rng.standard_normal((rows, K)) * np.exp2(rng.integers(-40, 40, (rows, K // 32)).repeat(32, axis=1).astype(np.float64))
+    V[0, :32] = 0.0                                       # an all-zero block
+    if rows > 2:
+        V[1, :32] = 0.0; V[1, 5] = 2.0 ** -3              # block maximum a power of two
+        V[2, :32] = 0.25; V[2, 7] = -np.nextafter(np.float32(1.0), np.float32(0))   # scaled maximum just below 512: saturates
+        V[2, 40:44] = [17.0, 18.0, 19.0, 0.0]             # (second block) ties between neighbouring codes
+    src = torch.from_numpy(V.astype(np.float32)).cuda().to(torch.bfloat16)
+    Vb = src.float().cpu().numpy().astype(np.float64)     # what the kernel receives
+    say("mx8 quantise rows=%d K=%d" % (rows, K))
+    codes, scales = L.moe_mx8_quantise(src)
+    torch.cuda.synchronize()
+    q_ref, s_ref = F.mx_quantise(Vb)
+    assert np.array_equal(unpack_scales(to_np(scales)), s_ref)
+    assert np.array_equal(to_np(codes), q_ref)
+
+
+def _case(T, d, E, k, f, seed):
+    cfg = scaled(CONFIGS["a3b_8k"], T=T, d=d, E=E, k=k, f=f, seed=seed)
+    inp = make_inputs(cfg)
+    idx, w, counts, offsets = O.route_topk(inp["logits"], k, 1)
+    row_of_pair, pair_of_row = O.permute_maps(idx, offsets)
+    return cfg, inp, offsets.astype(np.int32), pair_of_row.astype(np.int32)
+
+
+def _step_of_block(scales):
+    """one E4M3 step at the top binade of each block's range, as a value: 32 * 2^(s-127) (spacing of codes in [256, 448])"""
+    return 32.0 * np.exp2(scales.astype(np.float64) - 127.0)
+
+
+def _compare_forward(cfg, inp, offsets, pair_of_row, gather):
+    import torch
+    from paper_2508_02317_amd import libmoe as L
+    k = cfg.k
+    X = inp["X"].astype(np.float64)
+    Xq, Xs = F.mx_quantise(X)                              # by token
+    Wgq, Wgs = F.mx_quantise(inp["Wg"]); Wuq, Wus = F.mx_quantise(inp["Wu"]); Wdq, Wds = F.mx_quantise(inp["Wd"])
+    tok = pair_of_row // k
+    A = F.gate_up_fp8(Xq[tok], Xs[tok], Wgq, Wgs, Wuq, Wus, offsets)
+    Aq, As = F.quantise_activation(A)
+    Yp = F.down_fp8(Aq, As, Wdq, Wds, offsets)
+    E, f, d = inp["Wg"].shape
+    dev = lambda a: to_dev(np.ascontiguousarray(a))
+    wargs = (dev(Wgq), dev(pack_scales(Wgs.reshape(E * f, -1))), dev(Wuq), dev(pack_scales(Wus.reshape(E * f, -1))),
+             dev(Wdq), dev(pack_scales(Wds.reshape(E * d, -1))))
+    if gather:
+        actq, acts, yp = L.moe_grouped_gemm_swiglu_fwd_mx8(dev(Xq), dev(pack_scales(Xs)), *wargs, dev(offsets), pair_of_row=dev(pair_of_row), k=k)
+    else:
+        actq, acts, yp = L.moe_grouped_gemm_swiglu_fwd_mx8(dev(Xq[tok]), dev(pack_scales(Xs[tok])), *wargs, dev(offsets))
+    torch.cuda.synchronize()
+    got_s = unpack_scales(to_np(acts))
+    got_q = to_np(actq)
+    same_scale = got_s == As
+    frac_scale = 1.0 - same_scale.mean()
+    got_A = F.mx_dequantise(got_q, got_s)
+    ref_A = F.mx_dequantise(Aq, As)
+    step = np.maximum(_step_of_block(got_s), _step_of_block(As)).repeat(32, axis=1)
+    worst = np.max(np.abs(got_A - ref_A) / step)
+    frac_code = np.mean((got_q != Aq) | ~same_scale.repeat(32, axis=1))
+    err_a = rel_err(got_A, A)                              # against the unquantised activation: the quantisation error itself
+    err_y = rel_err(to_np(yp), Yp)
+    say("  gather=%s: act scales differing %.2e, codes differing %.2e, worst |dA| = %.2f steps, act vs fp64 act %.2e, Yp %.2e"
+        % (gather, frac_scale, frac_code, worst, err_a, err_y))
+    assert frac_scale <= 1e-3 and frac_code <= 5e-3
+    assert worst <= 1.0 + 1e-9
+    assert err_a <= 0.125 + 1e-3                           # the format's bound: saturation of a scaled maximum just below 512 to 448
+    assert err_y <= TOL["bf16"]
+    return to_np(actq), to_np(acts), to_np(yp)
+
+
+@pytest.mark.parametrize("T,d,E,k,f,seed", [(64, 128, 2, 1, 128, 0), (300, 256, 5, 2, 384, 1), (777, 384, 16, 2, 256, 2), (1500, 512, 4, 4, 768, 3)])
+def test_forward_products(T, d, E, k, f, seed):
+    cfg, inp, offsets, pair_of_row = _case(T, d, E, k, f, seed)
+    say("mx8 forward T=%d d=%d E=%d k=%d f=%d counts=%s" % (T, d, E, k, f, np.diff(offsets).tolist()))
+    a = _compare_forward(cfg, inp, offsets, pair_of_row, gather=False)
+    b = _compare_forward(cfg, inp, offsets, pair_of_row, gather=True)
+    for x, y in zip(a, b):                                 # reading rows by token changes nothing
+        assert np.array_equal(x, y)
+
+
+def test_forward_with_empty_experts_and_single_rows():
+    cfg, inp, _, _ = _case(40, 256, 8, 1, 256, 7)
+    idx = np.zeros((40, 1), dtype=np.int32); idx[0] = 3; idx[1:] = 6        # experts 0-2, 4, 5, 7 empty; expert 3 has one row
+    counts, offsets = O.counts_offsets(idx, 8)
+    _, pair_of_row = O.permute_maps(idx, offsets)
+    say("mx8 forward with empty experts counts=%s" % counts.tolist())
+    _compare_forward(cfg, inp, offsets.astype(np.int32), pair_of_row.astype(np.int32), gather=True)
+
+
+def test_rejects_unsupported_shapes():
+    import torch
+    from paper_2508_02317_amd import libmoe as L
+    with pytest.raises(L.MoEError) as e:
+        L.moe_mx8_quantise(torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda"))
+    assert e.value.code == 2 or "multiple of 128" in str(e.value)

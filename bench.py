@@ -33,6 +33,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 2048 MAC/clk x 2 x 2.4 GHz
 PEAK_FP32_TFLOPS = 157.3      # fp32 vector
+PEAK_FP8_TFLOPS = 5033.2      # dense fp8 MFMA (twice the bf16 rate)
 PEAK_HBM_GBS = 8000.0         # HBM3E
 PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (GPU model unstated), "
                  "mixed precision -- context only")
@@ -180,6 +181,63 @@ class LaunchTimer:
         return out
 
 
+def mx8_forward_leg(cfg, layer, x, wg, wu, wd, L, events, steps, warmup):
+    """The expert forward with 8-bit block-scaled operands (MXFP8), as a separate leg: quantise the layer input, then
+    the two products (rows read by token; the activation is quantised inside the first product).  The weights are
+    quantised once outside the timed region -- they change once per optimiser step, not per micro-batch -- and that
+    cost is reported beside it.  The routing of the bf16 step just run is reused."""
+    import torch
+    P, d, f, E = layer.P, cfg.d, cfg.f, cfg.E
+    stream = torch.cuda.current_stream().cuda_stream
+    timer = LaunchTimer(L, events)
+    torch.cuda.synchronize()
+    with timer:
+        wq = [L.moe_mx8_quantise(w) for w in (wg, wu, wd)]
+    torch.cuda.synchronize()
+    wprof, _ = timer.report()
+    xq = L.moe_mx8_quantise(x)
+    out = L.moe_grouped_gemm_swiglu_fwd_mx8(xq[0], xq[1], wq[0][0], wq[0][1], wq[1][0], wq[1][1], wq[2][0], wq[2][1], layer.offsets,
+                                            pair_of_row=layer.pair_of_row, k=cfg.k)
+    ws = torch.empty(L.lib.moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(P, d, f, E), dtype=torch.uint8, device=x.device)
+
+    def fwd():
+        L.moe_mx8_quantise(x, out=xq)
+        L.moe_grouped_gemm_swiglu_fwd_mx8(xq[0], xq[1], wq[0][0], wq[0][1], wq[1][0], wq[1][1], wq[2][0], wq[2][1], layer.offsets,
+                                          pair_of_row=layer.pair_of_row, k=cfg.k, out=out, ws=ws)
+    for _ in range(warmup):
+        fwd()
+    torch.cuda.synchronize()
+    a = events.record(stream)
+    for i in range(steps):
+        if i % SAMPLE_EVERY == 0:
+            with timer:
+                fwd()
+        else:
+            fwd()
+    b = events.record(stream)
+    ms = events.elapsed_ms(a, b) / steps
+    events.release([a, b])
+    prof, _ = timer.report()
+    dff = float(P) * d * f
+    flops = {"ffn_gate_up_mx8": 4 * dff, "ffn_down_mx8": 2 * dff}
+    kernels = {}
+    for name, (count, total) in prof.items():
+        avg = total / count
+        kernels[name] = {"avg_ms": round(avg, 5)}
+        if name in flops:
+            tf = flops[name] / (avg * 1e-3) / 1e12
+            kernels[name].update(bound="mfma", achieved=round(tf, 2), unit="TFLOP/s", peak=PEAK_FP8_TFLOPS, frac=round(tf / PEAK_FP8_TFLOPS, 4))
+        elif name == "mx8_quantise":
+            gbs = 3.0 * cfg.T * d / (avg * 1e-3) / 1e9          # 2 bytes read, 1 written per element
+            kernels[name].update(bound="hbm", achieved=round(gbs, 1), unit="GB/s", peak=PEAK_HBM_GBS, frac=round(gbs / PEAK_HBM_GBS, 4))
+    gemm_ms = sum(kernels[n]["avg_ms"] for n in flops if n in kernels)
+    return {"what": "expert forward (x quantise + gate/up + down) with MXFP8 operands, fp32 accumulation; never part of `value`",
+            "ms_per_forward": round(ms, 4), "kernels": kernels,
+            "grouped_gemm": {"ms": round(gemm_ms, 4), "tflops": round(6 * dff / (gemm_ms * 1e-3) / 1e12, 2),
+                             "frac_of_peak": round(6 * dff / (gemm_ms * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 4), "peak": PEAK_FP8_TFLOPS},
+            "weight_quantise_ms_outside_timed_region": round(sum(t for _, t in wprof.values()), 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -198,6 +256,7 @@ def main():
                     help="call moe_permute, moe_grouped_gemm_swiglu_fwd/bwd and moe_unpermute_combine_bwd separately, "
                          "writing the expert-ordered copies xp and dyp (the default step uses the *_gather entry points, "
                          "which read the layer input and the output gradient by token inside the products)")
+    ap.add_argument("--no-mx8", action="store_true", help="skip the separate 8-bit forward leg (key `mx8_forward` of the line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -400,6 +459,10 @@ def main():
         "context": PAPER_CONTEXT,
     }
 
+    if not args.no_mx8 and cfg.dtype == "bf16" and cfg.d % 128 == 0 and cfg.f % 128 == 0:
+        bf16_fwd = sum(kernels[n]["avg_ms"] for n in ("ffn_gate_up", "ffn_down") if n in kernels)
+        out["mx8_forward"] = mx8_forward_leg(cfg, layer, x, wg, wu, wd, L, events, args.steps, args.warmup)
+        out["mx8_forward"]["bf16_products_ms_for_comparison"] = round(bf16_fwd, 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp, Xh, layer, prerouted,
                                            (lidx, lw) if prerouted else None)

@@ -109,8 +109,14 @@ int32_t moe_route_topk(const float* logits, int T, int E, int k, int renorm,
  *   d and f must be multiples of 128; T * d < 2^32 when rows are read by token.  ws, ws_bytes: device workspace of
  *   at least moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(P, d, f, E).
  * Errors as everywhere: INVALID_ARG / UNSUPPORTED / WORKSPACE mean nothing was launched.
+ *
+ * moe_grouped_gemm_down_mx8: the second product alone, yp = act Wd[e]^T, on activation codes and scales the caller
+ *   supplies (actq [P, f] and acts [f/128][P] in, read only); everything else as above, same workspace size.
  */
 int32_t moe_mx8_quantise(const void* src, int64_t rows, int K, void* codes, void* scales, void* stream);
+int32_t moe_grouped_gemm_down_mx8(const void* actq, const void* acts, const void* wdq, const void* wds, int P, int d,
+                                  int f, int E, const int32_t* offsets, void* yp, void* ws, size_t ws_bytes,
+                                  void* stream);
 size_t moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(int P, int d, int f, int E);
 int32_t moe_grouped_gemm_swiglu_fwd_mx8(const void* xq, const void* xs, int T, int k, const int32_t* pair_of_row,
                                         const void* wgq, const void* wgs, const void* wuq, const void* wus,

@@ -243,6 +243,22 @@ extern "C" int32_t moe_grouped_gemm_swiglu_fwd_mx8(const void* xq, const void* x
   return end_call();
 }
 
+extern "C" int32_t moe_grouped_gemm_down_mx8(const void* actq, const void* acts, const void* wdq, const void* wds, int P, int d, int f,
+                                            int E, const int32_t* offsets, void* yp, void* ws, size_t ws_bytes, void* stream) {
+  if (int32_t rc = check_mx8_dims(P, d, f, E, 0, 1, false)) return rc;
+  if (P == 0) return MOE_OK;
+  MOE_REQUIRE(actq && acts && wdq && wds && offsets && yp, MOE_ERR_INVALID_ARG, "down_mx8: null pointer");
+  MOE_REQUIRE(aligned16(actq) && aligned16(acts) && aligned16(wdq) && aligned16(wds) && aligned16(yp), MOE_ERR_INVALID_ARG,
+              "down_mx8: tensors must be 16-byte aligned");
+  const size_t need = moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(P, d, f, E);
+  MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "down_mx8: workspace null, misaligned or smaller than %zu bytes", need);
+  FfnFwdMx8Args a{nullptr, nullptr, P, 1, nullptr, nullptr, nullptr, nullptr, nullptr, wdq, wds, P, d, f, E, offsets,
+                  const_cast<void*>(actq), const_cast<void*>(acts), yp, ws, static_cast<hipStream_t>(stream)};
+  begin_call("moe_grouped_gemm_down_mx8", static_cast<hipStream_t>(stream));
+  ffn_fwd_mx8(a);
+  return end_call();
+}
+
 // ---- router linear -----------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, size_t n) {
   const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;

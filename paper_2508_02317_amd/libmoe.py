@@ -31,6 +31,7 @@ EXPORTS = [
     "moe_unpermute_combine_fwd", "moe_unpermute_combine_bwd",
     "moe_router_logits_workspace_bytes", "moe_router_logits", "moe_router_bwd_workspace_bytes", "moe_router_bwd",
     "moe_mx8_quantise", "moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes", "moe_grouped_gemm_swiglu_fwd_mx8",
+    "moe_grouped_gemm_down_mx8",
     "moe_set_launch_hook",
 ]
 
@@ -108,6 +109,8 @@ def _load():
     lib.moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.moe_grouped_gemm_swiglu_fwd_mx8.restype = ctypes.c_int32
     lib.moe_grouped_gemm_swiglu_fwd_mx8.argtypes = [vp, vp, i32, i32, vp] + [vp] * 6 + [i32] * 4 + [vp] * 5 + [sz, vp]
+    lib.moe_grouped_gemm_down_mx8.restype = ctypes.c_int32
+    lib.moe_grouped_gemm_down_mx8.argtypes = [vp] * 4 + [i32] * 4 + [vp] * 3 + [sz, vp]
     lib.moe_set_launch_hook.restype = ctypes.c_int32
     lib.moe_set_launch_hook.argtypes = [LAUNCH_HOOK, vp]
     return lib
@@ -337,6 +340,19 @@ def moe_grouped_gemm_swiglu_fwd_mx8(xq, xs, wgq, wgs, wuq, wus, wdq, wds, offset
                                                _ptr(wdq), _ptr(wds), P, d, f, E, _ptr(offsets), _ptr(actq), _ptr(acts), _ptr(yp),
                                                _ptr(ws), nbytes, _stream()))
     return actq, acts, yp
+
+
+def moe_grouped_gemm_down_mx8(actq, acts, wdq, wds, offsets, out=None, ws=None):
+    """The second product alone on given activation codes [P, f] and scale words [f/128, P].  -> yp bf16 [P, d]."""
+    _need(actq, torch.uint8, "actq"); _need(acts, torch.int32, "acts"); _need(wdq, torch.uint8, "wdq"); _need(wds, torch.int32, "wds")
+    _need(offsets, torch.int32, "offsets")
+    P, f = actq.shape
+    E, d, _ = wdq.shape
+    yp = out if out is not None else torch.empty((P, d), dtype=torch.bfloat16, device=actq.device)
+    ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(P, d, f, E), ws, actq.device)
+    _check(lib.moe_grouped_gemm_down_mx8(_ptr(actq), _ptr(acts), _ptr(wdq), _ptr(wds), P, d, f, E, _ptr(offsets), _ptr(yp),
+                                         _ptr(ws), nbytes, _stream()))
+    return yp
 
 
 def moe_grouped_gemm_swiglu_bwd_gather(dy, x, topk_w, pair_of_row, g_save, u_save, w_gate, w_up, w_down, offsets,

@@ -40,7 +40,7 @@ PAPER_CONTEXT = ("paper: >2,800 tokens/sec/GPU, 30B MoE, whole model, 128 GPUs (
 SAMPLE_EVERY = 5              # steps between two steps whose launches are bracketed by events
 
 
-def kernel_work(cfg, P, gather, save_gu):
+def kernel_work(cfg, P, gather, save_gu, late_weight=False):
     """Per kernel: (bound, algorithmic amount per launch, compulsory HBM bytes per launch or None).
 
     Flops count routed work only.  The compulsory bytes of a product are its operands read once and its
@@ -58,7 +58,7 @@ def kernel_work(cfg, P, gather, save_gu):
     work = {
         pre + "gate_up": (mm, 4 * dff, xin + 2 * Edf + gu_out),
         pre + "down": (mm, 2 * dff, Pf + Edf + Pd),
-        pre + "dact": (mm, 2 * dff, xin + Edf + 2 * Pf + 2 * Pf + (Pf if gather else 0)),
+        pre + "dact": (mm, 2 * dff, xin + Edf + 2 * Pf + 2 * Pf + (Pf if late_weight else 0)),   # + w * act out if the forward did not write it
         pre + "dx": (mm, 4 * dff, 2 * Pf + 2 * Edf + Pd),
         "wgrad_down": (mm, 2 * dff, xin + Pf + Edf),
         "wgrad_gate_up": (mm, 4 * dff, 2 * Pf + xin + 2 * Edf),
@@ -256,6 +256,9 @@ def main():
                     help="call moe_permute, moe_grouped_gemm_swiglu_fwd/bwd and moe_unpermute_combine_bwd separately, "
                          "writing the expert-ordered copies xp and dyp (the default step uses the *_gather entry points, "
                          "which read the layer input and the output gradient by token inside the products)")
+    ap.add_argument("--weight-in-combine", action="store_true",
+                    help="gathered step only: leave the combine weight to moe_unpermute_combine_fwd (the backward then forms and "
+                         "stores w * act itself); the default applies it inside the forward products")
     ap.add_argument("--no-mx8", action="store_true", help="skip the separate 8-bit forward leg (key `mx8_forward` of the line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for scaling the "
@@ -309,7 +312,8 @@ def main():
         w_router = dev(np.ascontiguousarray(inp["Wr"].T))             # [E, d]
     gather, save_gu = not args.no_gather, not args.no_save_gu
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, wg, wu, wd, renorm=cfg.renorm, prerouted=prerouted,
-                     save_gu=save_gu, w_router=w_router, gather=gather)
+                     save_gu=save_gu, w_router=w_router, gather=gather,
+                     weight_in_forward=(gather and not args.weight_in_combine))
     P = layer.P
     print("[bench] %s: inputs ready in %.1f s" % (cfg.name, time.time() - t0), file=sys.stderr, flush=True)
 
@@ -382,7 +386,7 @@ def main():
     torch.cuda.synchronize()
     ms_per_step_without_events = (time.perf_counter() - t_plain) * 1e3 / args.steps
 
-    work = kernel_work(cfg, P, gather, save_gu)
+    work = kernel_work(cfg, P, gather, save_gu, late_weight=gather and not layer.weight_in_forward)
     traffic, traffic_source = measured_traffic(cfg.name, gather) if (save_gu and not args.router) else ({}, None)
     kernels = {}
     for name, (count, total_ms) in prof.items():
@@ -439,7 +443,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "k": cfg.k, "f": cfg.f, "P": P,
                    "renorm": cfg.renorm, "save_gu": save_gu, "router_linear_in_step": bool(args.router), "hip_graph": bool(args.graph),
-                   "gather_in_gemm": gather,
+                   "gather_in_gemm": gather, "combine_weight_in_forward_products": bool(layer.weight_in_forward),
                    "kernel_events": ("every %dth timed step" % SAMPLE_EVERY) if events_in_timed_region else "second pass",
                    "unit_note": "routed rows/s" if prerouted else "tokens/s",
                    # weights and their gradients, the token-major and the expert-ordered activations: under 256 MB the

@@ -217,6 +217,10 @@ int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, const void*
  *
  * Forward: exactly moe_grouped_gemm_swiglu_fwd applied to xp[r] = x[pair_of_row[r] / k].
  *   x [T,d] in; pair_of_row [P] in (from moe_permute); the rest as in moe_grouped_gemm_swiglu_fwd.
+ *   topk_w [T,k] f32 in, or NULL.  Given, the combine weight is applied here instead of in the combine:
+ *   act[r] = topk_w[pair] * silu(G) * U (scaled in fp32, rounded once) and yp[r] = act[r] W_down[e]^T
+ *   = topk_w[pair] * FFN(x[token]), so that Y is moe_unpermute_combine_fwd of yp with NULL weights and the
+ *   backward finds its operand topk_w * act already written (act_w below).  g_save, u_save stay unscaled.
  *
  * Backward: exactly moe_unpermute_combine_bwd followed by moe_grouped_gemm_swiglu_bwd, i.e. with
  * dyp[r] = topk_w[pair] * dy[token] never stored:
@@ -224,12 +228,15 @@ int32_t moe_grouped_gemm_swiglu_bwd(const void* dyp, const void* xp, const void*
  *   dtopk_w[pair] = <dy[token] W_down[e], act[r]>  ( = <dy[token], yp[r]> );
  *   dG, dU, dW_gate, dW_up, dxp as in moe_grouped_gemm_swiglu_bwd with xp[r] = x[token].
  *   dy, x [T,d] in; topk_w [T,k] f32 in; g_save, u_save [P,f] in, or both NULL (recomputed from x);
+ *   act_w [P,f] in, or NULL: topk_w[pair] * act as the forward with topk_w wrote it into `act`; NULL: it is
+ *   formed here and staged in the workspace (one more [P,f] store);
  *   dxp [P,d] out (moe_unpermute_combine_fwd with NULL weights turns it into dx); dw_* out;
  *   dtopk_w [T,k] f32 out (input of moe_route_topk_bwd).  act and yp are not needed.
  * For bf16, act is recomputed from the rounded G and U in fp32, and topk_w * act is rounded once.
  */
 size_t moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(int dtype, int P, int d, int f, int E);
 int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int k, const int32_t* pair_of_row,
+                                           const float* topk_w,
                                            const void* w_gate, const void* w_up, const void* w_down,
                                            int dtype, int P, int d, int f, int E, const int32_t* offsets,
                                            void* g_save, void* u_save, void* act, void* yp,
@@ -237,7 +244,7 @@ int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int k, const in
 size_t moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(int dtype, int P, int d, int f, int E, int have_saved);
 int32_t moe_grouped_gemm_swiglu_bwd_gather(const void* dy, const void* x, int T, int k, const float* topk_w,
                                            const int32_t* pair_of_row, const void* g_save,
-                                           const void* u_save, const void* w_gate, const void* w_up,
+                                           const void* u_save, const void* act_w, const void* w_gate, const void* w_up,
                                            const void* w_down, int dtype, int P, int d, int f, int E,
                                            const int32_t* offsets, void* dxp, void* dw_gate, void* dw_up,
                                            void* dw_down, float* dtopk_w, void* ws, size_t ws_bytes,

@@ -152,10 +152,10 @@ extern "C" size_t moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(int dtype, 
   return dtype == MOE_BF16 ? ffn_bwd_gather_ws_bytes_bf16(P, d, f, E, have_saved) : ffn_bwd_gather_ws_bytes_f32(P, d, f, E, have_saved);
 }
 
-extern "C" int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int k, const int32_t* pair_of_row, const void* w_gate,
-                                                      const void* w_up, const void* w_down, int dtype, int P, int d, int f, int E,
-                                                      const int32_t* offsets, void* g_save, void* u_save, void* act, void* yp,
-                                                      void* ws, size_t ws_bytes, void* stream) {
+extern "C" int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int k, const int32_t* pair_of_row, const float* topk_w,
+                                                      const void* w_gate, const void* w_up, const void* w_down, int dtype, int P,
+                                                      int d, int f, int E, const int32_t* offsets, void* g_save, void* u_save,
+                                                      void* act, void* yp, void* ws, size_t ws_bytes, void* stream) {
   if (int32_t rc = check_ffn_dims("ffn_fwd_gather", dtype, P, d, f, E)) return rc;
   if (int32_t rc = check_gather_dims("ffn_fwd_gather", dtype, T, k, P, d)) return rc;
   MOE_REQUIRE((g_save == nullptr) == (u_save == nullptr), MOE_ERR_INVALID_ARG, "ffn_fwd_gather: g_save and u_save must both be given or both be null");
@@ -166,7 +166,7 @@ extern "C" int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int 
   const size_t need = moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(dtype, P, d, f, E);
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_fwd_gather: workspace null, misaligned or smaller than %zu bytes", need);
   FfnFwdGatherArgs a{x, T, k, pair_of_row, w_gate, w_up, w_down, P, d, f, E, offsets, g_save, u_save, act, yp, ws,
-                     static_cast<hipStream_t>(stream)};
+                     static_cast<hipStream_t>(stream), topk_w};
   begin_call("moe_grouped_gemm_swiglu_fwd_gather", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) ffn_fwd_gather_bf16(a); else ffn_fwd_gather_f32(a);
   return end_call();
@@ -174,23 +174,23 @@ extern "C" int32_t moe_grouped_gemm_swiglu_fwd_gather(const void* x, int T, int 
 
 extern "C" int32_t moe_grouped_gemm_swiglu_bwd_gather(const void* dy, const void* x, int T, int k, const float* topk_w,
                                                       const int32_t* pair_of_row, const void* g_save, const void* u_save,
-                                                      const void* w_gate, const void* w_up, const void* w_down, int dtype, int P,
-                                                      int d, int f, int E, const int32_t* offsets, void* dxp, void* dw_gate,
-                                                      void* dw_up, void* dw_down, float* dtopk_w, void* ws, size_t ws_bytes,
-                                                      void* stream) {
+                                                      const void* act_w, const void* w_gate, const void* w_up, const void* w_down,
+                                                      int dtype, int P, int d, int f, int E, const int32_t* offsets, void* dxp,
+                                                      void* dw_gate, void* dw_up, void* dw_down, float* dtopk_w, void* ws,
+                                                      size_t ws_bytes, void* stream) {
   if (int32_t rc = check_ffn_dims("ffn_bwd_gather", dtype, P, d, f, E)) return rc;
   if (int32_t rc = check_gather_dims("ffn_bwd_gather", dtype, T, k, P, d)) return rc;
   MOE_REQUIRE((g_save == nullptr) == (u_save == nullptr), MOE_ERR_INVALID_ARG, "ffn_bwd_gather: g_save and u_save must both be given or both be null");
   MOE_REQUIRE(offsets && dw_gate && dw_up && dw_down, MOE_ERR_INVALID_ARG, "ffn_bwd_gather: null offsets or weight-gradient pointer");
   MOE_REQUIRE(P == 0 || (dy && x && topk_w && pair_of_row && w_gate && w_up && w_down && dxp && dtopk_w), MOE_ERR_INVALID_ARG,
               "ffn_bwd_gather: null pointer");
-  MOE_REQUIRE(aligned16(dy) && aligned16(x) && aligned16(g_save) && aligned16(u_save) && aligned16(w_gate) && aligned16(w_up) &&
+  MOE_REQUIRE(aligned16(dy) && aligned16(x) && aligned16(g_save) && aligned16(u_save) && aligned16(act_w) && aligned16(w_gate) && aligned16(w_up) &&
               aligned16(w_down) && aligned16(dxp) && aligned16(dw_gate) && aligned16(dw_up) && aligned16(dw_down),
               MOE_ERR_INVALID_ARG, "ffn_bwd_gather: tensors must be 16-byte aligned");
   const size_t need = moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(dtype, P, d, f, E, g_save != nullptr);
   MOE_REQUIRE(ws && ws_bytes >= need && aligned16(ws), MOE_ERR_WORKSPACE, "ffn_bwd_gather: workspace null, misaligned or smaller than %zu bytes", need);
   FfnBwdGatherArgs a{dy, x, T, k, topk_w, pair_of_row, g_save, u_save, w_gate, w_up, w_down, P, d, f, E, offsets, dxp, dw_gate,
-                     dw_up, dw_down, dtopk_w, ws, static_cast<hipStream_t>(stream)};
+                     dw_up, dw_down, dtopk_w, ws, static_cast<hipStream_t>(stream), act_w};
   begin_call("moe_grouped_gemm_swiglu_bwd_gather", static_cast<hipStream_t>(stream));
   if (dtype == MOE_BF16) ffn_bwd_gather_bf16(a); else ffn_bwd_gather_f32(a);
   return end_call();

@@ -842,7 +842,8 @@ struct RowArgs {
   // FUSED kernels: `a` is the token-major matrix [T, lda] and row r of the product reads a[row_token[r]]
   const int32_t* row_token;    // [P (+ padding)]
   const float* row_w;          // kDAct: combine weight of each row; the product's rows are scaled by it
-  bf16_t* act_w;               // kDAct: [P, N] out, row_w * silu(G) * U
+                               // kGateUp (may be null): the activation leaves scaled by it
+  bf16_t* act_w;               // kDAct: [P, N] out, row_w * silu(G) * U; null: not written (the forward left it)
   float* dw_partial;           // kDAct: [n_tiles_n * WGN][P] out, partial sums of <silu(G) * U, unscaled dA> per row
 };
 
@@ -918,7 +919,12 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
     for (int mi = 0; mi < MI; ++mi) {
       if (mi >= mi_n) break;
       park_strip<T>(acc[mi], strip, el);
-      float g[NP][8], u[NP][8];
+      float g[NP][8], u[NP][8], wr[NP];
+#pragma unroll
+      for (int pass = 0; pass < NP; ++pass) {           // the rows' combine weights, if the activation is to carry them
+        const int r = wm * WM + mi * 32 + pass * RPP + el / LPR;
+        wr[pass] = p.row_w ? p.row_w[row0 + (r < rows ? r : 0)] : 1.0f;
+      }
 #pragma unroll
       for (int pass = 0; pass < NP; ++pass) {
         const int rs = pass * RPP + el / LPR;
@@ -931,7 +937,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
         if (cl < ncols && r < rows) {
           float a[8];
 #pragma unroll
-          for (int q = 0; q < 8; ++q) a[q] = g[pass][q] * sigmoid_fast(g[pass][q]) * u[pass][q];
+          for (int q = 0; q < 8; ++q) a[q] = wr[pass] * (g[pass][q] * sigmoid_fast(g[pass][q]) * u[pass][q]);
           const long o = static_cast<long>(row0 + r) * p.ldo + n0 + cl;
           if (p.out0) store16(p.out0 + o, pack8(g[pass]));
           if (p.out1) store16(p.out1 + o, pack8(u[pass]));
@@ -1024,7 +1030,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
               if (live) {
                 store16(p.out0 + o, pack8(dg));
                 store16(p.out0 + o + p.N, pack8(du));
-                store16(p.act_w + gi, pack8(aw));
+                if (p.act_w) store16(p.act_w + gi, pack8(aw));
               } else {
                 part = 0.0f;
               }
@@ -1564,9 +1570,10 @@ static void launch_wgrad(const WgradArgs& p, hipStream_t s) {
 // row_token == null: xp is in expert order; else xp is the token-major input and rows are gathered from it
 static void launch_gate_up(const void* xp, const void* wg, const void* wu, int P, int d, int f, int E,
                            const int32_t* offsets, const RowTiles& rt, void* G, void* U, void* act, hipStream_t s,
-                           const int32_t* row_token = nullptr) {
+                           const int32_t* row_token = nullptr, const float* row_w = nullptr) {
   RowArgs p{};
   p.row_token = row_token;
+  p.row_w = row_w;
   p.a = static_cast<const bf16_t*>(xp); p.lda = d;
   p.w0 = static_cast<const bf16_t*>(wg); p.w1 = static_cast<const bf16_t*>(wu);
   p.w_expert_stride = static_cast<long>(f) * d; p.ldw = d;
@@ -1673,9 +1680,9 @@ static GatherWs gather_ws(const WsLayout& w, int P, int f, bool bwd) {
   GatherWs g{};
   size_t off = w.total;
   g.row_token = off; off += align_up(static_cast<size_t>(P + kRowTokenPad) * sizeof(int32_t), 256);
-  g.row_w = off; g.act_w = off; g.dw_partial = off;
+  g.row_w = off; off += align_up(static_cast<size_t>(P) * sizeof(float), 256);
+  g.act_w = off; g.dw_partial = off;
   if (bwd) {
-    off += align_up(static_cast<size_t>(P) * sizeof(float), 256);
     g.act_w = off; off += align_up(static_cast<size_t>(P) * f * 2, 256);
     g.dw_partial = off; off += align_up(static_cast<size_t>(dw_slots(f)) * P * sizeof(float), 256);
   }
@@ -1694,13 +1701,16 @@ void ffn_fwd_gather_bf16(const FfnFwdGatherArgs& a) {
   const GatherWs g = gather_ws(w, a.P, a.f, false);
   const RowTiles rt = row_tiles_at(a.ws, w, a.P, a.E);
   int32_t* row_token = reinterpret_cast<int32_t*>(static_cast<char*>(a.ws) + g.row_token);
+  float* row_w = reinterpret_cast<float*>(static_cast<char*>(a.ws) + g.row_w);
   {
     ScheduleArgs sa{};
     sa.offsets = a.offsets; sa.E = a.E; sa.P = a.P; sa.bm = row_bm(); sa.rt = rt;
     sa.pair_of_row = a.pair_of_row; sa.T = a.T; sa.k = a.k; sa.row_token = row_token;
+    if (a.topk_w) { sa.topk_w = a.topk_w; sa.row_w = row_w; }
     launch_schedules(sa, a.stream);
   }
-  launch_gate_up(a.x, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.g_save, a.u_save, a.act, a.stream, row_token);
+  launch_gate_up(a.x, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.g_save, a.u_save, a.act, a.stream, row_token,
+                 a.topk_w ? row_w : nullptr);
   launch_down(a.act, a.w_down, a.P, a.d, a.f, a.E, a.offsets, rt, a.yp, a.stream);
 }
 
@@ -1713,7 +1723,8 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
   bf16_t* dgu = reinterpret_cast<bf16_t*>(base + w.dgu);       // [P, 2f] = [dG | dU]
   int32_t* row_token = reinterpret_cast<int32_t*>(base + gw.row_token);
   float* row_w = reinterpret_cast<float*>(base + gw.row_w);
-  bf16_t* act_w = reinterpret_cast<bf16_t*>(base + gw.act_w);
+  bf16_t* act_w_ws = reinterpret_cast<bf16_t*>(base + gw.act_w);
+  const bf16_t* act_w = a.act_w ? static_cast<const bf16_t*>(a.act_w) : act_w_ws;
   float* dw_partial = reinterpret_cast<float*>(base + gw.dw_partial);
   const bf16_t* G = static_cast<const bf16_t*>(a.g_save);
   const bf16_t* U = static_cast<const bf16_t*>(a.u_save);
@@ -1737,7 +1748,7 @@ void ffn_bwd_gather_bf16(const FfnBwdGatherArgs& a) {
     p.w0 = static_cast<const bf16_t*>(a.w_down); p.w_expert_stride = static_cast<long>(a.d) * a.f; p.ldw = a.f;
     p.K = a.d; p.N = a.f; p.offsets = a.offsets; p.P = a.P; p.rt = rt; p.zeros = reinterpret_cast<const bf16_t*>(rt.zeros);
     p.out0 = dgu; p.ldo = 2L * a.f; p.g = G; p.u = U;
-    p.row_token = row_token; p.row_w = row_w; p.act_w = act_w; p.dw_partial = dw_partial;
+    p.row_token = row_token; p.row_w = row_w; p.act_w = a.act_w ? nullptr : act_w_ws; p.dw_partial = dw_partial;
     launch_row<kDAct, true>(p, a.P, a.E, a.stream);
   }
   launch_dx(dgu, a.w_gate, a.w_up, a.P, a.d, a.f, a.E, a.offsets, rt, a.dxp, a.stream);

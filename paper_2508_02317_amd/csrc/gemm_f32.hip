@@ -26,7 +26,8 @@ __device__ __forceinline__ int expert_of_row(const int32_t* __restrict__ offsets
 __global__ __launch_bounds__(kF32Threads) void f32_gate_up_kernel(
     const float* __restrict__ xp, const float* __restrict__ wg, const float* __restrict__ wu,
     int P, int d, int f, int E, const int32_t* __restrict__ offsets,
-    float* __restrict__ G, float* __restrict__ U, float* __restrict__ act, const int32_t* __restrict__ row_src) {
+    float* __restrict__ G, float* __restrict__ U, float* __restrict__ act, const int32_t* __restrict__ row_src,
+    const float* __restrict__ row_w) {
   const size_t i = static_cast<size_t>(blockIdx.x) * kF32Threads + threadIdx.x;
   if (i >= static_cast<size_t>(P) * f) return;
   const int r = static_cast<int>(i / f), n = static_cast<int>(i % f);
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(kF32Threads) void f32_gate_up_kernel(
   for (int c = 0; c < d; ++c) { g = fmaf(x[c], g_row[c], g); u = fmaf(x[c], u_row[c], u); }
   if (G) G[i] = g;
   if (U) U[i] = u;
-  if (act) act[i] = g * sigmoid_acc(g) * u;
+  if (act) act[i] = (row_w ? row_w[r] : 1.0f) * (g * sigmoid_acc(g) * u);      // row_w: the activation carries the combine weight
 }
 
 // yp = act Wd^T                                         one thread per (row, c)
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(kF32Threads) void f32_dact_kernel(
   const float s = sigmoid_acc(g);
   if (row_w) {   // the rows of dyp are w_r * dy[token]: scale the product instead, and keep what the combine backward needs
     dA_unscaled[i] = da;
-    act_w[i] = row_w[r] * (g * s * u);
+    if (act_w) act_w[i] = row_w[r] * (g * s * u);
     da *= row_w[r];
   }
   dG[i] = da * u * (s * (1.0f + g * (1.0f - s)));
@@ -161,7 +162,7 @@ void ffn_fwd_f32(const FfnFwdArgs& a) {
                      static_cast<const float*>(a.xp), static_cast<const float*>(a.w_gate),
                      static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets,
                      static_cast<float*>(a.g_save), static_cast<float*>(a.u_save), static_cast<float*>(a.act),
-                     static_cast<const int32_t*>(nullptr));
+                     static_cast<const int32_t*>(nullptr), static_cast<const float*>(nullptr));
   if (a.yp)
     MOE_LAUNCH("f32_down", f32_down_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream,
                        static_cast<const float*>(a.act), static_cast<const float*>(a.w_down), a.P, a.d, a.f, a.E,
@@ -183,7 +184,7 @@ void ffn_bwd_f32(const FfnBwdArgs& a) {
       MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
                          static_cast<const float*>(a.xp), static_cast<const float*>(a.w_gate),
                          static_cast<const float*>(a.w_up), a.P, a.d, a.f, a.E, a.offsets, Gr, Ur,
-                         static_cast<float*>(nullptr), static_cast<const int32_t*>(nullptr));
+                         static_cast<float*>(nullptr), static_cast<const int32_t*>(nullptr), static_cast<const float*>(nullptr));
       G = Gr; U = Ur;
     }
     MOE_LAUNCH("f32_dact", f32_dact_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
@@ -213,7 +214,7 @@ void ffn_bwd_f32(const FfnBwdArgs& a) {
 // ---- the variants that read the layer input / the output gradient by token -------------------------
 // workspace: [256 | row_token P i32 | row_w P f32 | dG | dU | dA_unscaled | act_w | (G | U)], each aligned to 256
 static size_t f32_list_bytes(int P) { return align_up(static_cast<size_t>(P) * 4, 256); }
-size_t ffn_fwd_gather_ws_bytes_f32(int P, int, int, int) { return 256 + f32_list_bytes(P); }
+size_t ffn_fwd_gather_ws_bytes_f32(int P, int, int, int) { return 256 + 2 * f32_list_bytes(P); }
 size_t ffn_bwd_gather_ws_bytes_f32(int P, int d, int f, int E, int have_saved) {
   (void)d; (void)E;
   const size_t pf = align_up(static_cast<size_t>(P) * f * sizeof(float), 256);
@@ -224,12 +225,13 @@ void ffn_fwd_gather_f32(const FfnFwdGatherArgs& a) {
   if (a.P == 0) return;
   const size_t pf = static_cast<size_t>(a.P) * a.f, pd = static_cast<size_t>(a.P) * a.d;
   int32_t* row_token = reinterpret_cast<int32_t*>(static_cast<char*>(a.ws) + 256);
+  float* row_w = a.topk_w ? reinterpret_cast<float*>(static_cast<char*>(a.ws) + 256 + f32_list_bytes(a.P)) : nullptr;
   MOE_LAUNCH("f32_row_token", f32_row_token_kernel, dim3(blocks_for(a.P)), dim3(kF32Threads), 0, a.stream, a.pair_of_row,
-             static_cast<const float*>(nullptr), a.P, a.T, a.k, row_token, static_cast<float*>(nullptr));
+             a.topk_w, a.P, a.T, a.k, row_token, row_w);
   MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
              static_cast<const float*>(a.x), static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d, a.f,
              a.E, a.offsets, static_cast<float*>(a.g_save), static_cast<float*>(a.u_save), static_cast<float*>(a.act),
-             static_cast<const int32_t*>(row_token));
+             static_cast<const int32_t*>(row_token), static_cast<const float*>(row_w));
   MOE_LAUNCH("f32_down", f32_down_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(a.act),
              static_cast<const float*>(a.w_down), a.P, a.d, a.f, a.E, a.offsets, static_cast<float*>(a.yp));
 }
@@ -244,7 +246,8 @@ void ffn_bwd_gather_f32(const FfnBwdGatherArgs& a) {
   float* dG = reinterpret_cast<float*>(big);
   float* dU = reinterpret_cast<float*>(big + pf_bytes);
   float* dA = reinterpret_cast<float*>(big + 2 * pf_bytes);
-  float* act_w = reinterpret_cast<float*>(big + 3 * pf_bytes);
+  float* act_w_ws = reinterpret_cast<float*>(big + 3 * pf_bytes);
+  const float* act_w = a.act_w ? static_cast<const float*>(a.act_w) : act_w_ws;
   const float* G = static_cast<const float*>(a.g_save);
   const float* U = static_cast<const float*>(a.u_save);
   if (a.P > 0) {
@@ -255,12 +258,12 @@ void ffn_bwd_gather_f32(const FfnBwdGatherArgs& a) {
       float* Ur = reinterpret_cast<float*>(big + 5 * pf_bytes);
       MOE_LAUNCH("f32_gate_up", f32_gate_up_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream,
                  static_cast<const float*>(a.x), static_cast<const float*>(a.w_gate), static_cast<const float*>(a.w_up), a.P, a.d,
-                 a.f, a.E, a.offsets, Gr, Ur, static_cast<float*>(nullptr), static_cast<const int32_t*>(row_token));
+                 a.f, a.E, a.offsets, Gr, Ur, static_cast<float*>(nullptr), static_cast<const int32_t*>(row_token), static_cast<const float*>(nullptr));
       G = Gr; U = Ur;
     }
     MOE_LAUNCH("f32_dact", f32_dact_kernel, dim3(blocks_for(pf)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(a.dy),
                static_cast<const float*>(a.w_down), G, U, a.P, a.d, a.f, a.E, a.offsets, dG, dU,
-               static_cast<const int32_t*>(row_token), static_cast<const float*>(row_w), dA, act_w);
+               static_cast<const int32_t*>(row_token), static_cast<const float*>(row_w), dA, a.act_w ? static_cast<float*>(nullptr) : act_w_ws);
     MOE_LAUNCH("f32_dw", f32_dw_kernel, dim3(blocks_for(static_cast<size_t>(a.P) * 64)), dim3(kF32Threads), 0, a.stream, static_cast<const float*>(dA), G, U,
                a.P, a.f, a.pair_of_row, a.dtopk_w);
     MOE_LAUNCH("f32_dx", f32_dx_kernel, dim3(blocks_for(pd)), dim3(kF32Threads), 0, a.stream, dG, dU,

@@ -110,6 +110,7 @@ struct FfnFwdGatherArgs {
   void *g_save, *u_save, *act, *yp;   // g_save/u_save may be null
   void* ws;
   hipStream_t stream;
+  const float* topk_w;                // [T, k] or null; given: act and yp leave scaled by the row's combine weight
 };
 struct FfnBwdGatherArgs {
   const void *dy, *x;                 // [T, d]
@@ -123,6 +124,7 @@ struct FfnBwdGatherArgs {
   float* dtopk_w;                     // [T, k]
   void* ws;
   hipStream_t stream;
+  const void* act_w;                  // [P, f] or null: w * act as the weighted forward left it (null: formed here)
 };
 // 8-bit (MXFP8) operands: quantiser and forward products
 struct Mx8QuantArgs {

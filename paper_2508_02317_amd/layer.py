@@ -7,6 +7,8 @@ Backward: moe_unpermute_combine_bwd -> moe_grouped_gemm_swiglu_bwd -> moe_unperm
 With gather=True the two copies into expert order disappear (xp and dyp are never written):
 Forward:  moe_route_topk -> moe_permute (maps only) -> moe_grouped_gemm_swiglu_fwd_gather -> moe_unpermute_combine_fwd
 Backward: moe_grouped_gemm_swiglu_bwd_gather -> moe_unpermute_combine_fwd (unit weights) -> moe_route_topk_bwd
+and, with weight_in_forward (the default of the gathered path), the combine weight is applied inside the forward
+products (act and yp leave scaled by it), so the forward combine is a plain sum and the backward finds w * act written.
 
 Nothing is computed here; every step is a call into libmoe on the current stream, with no
 host synchronisation in between, and no allocation after construction.
@@ -25,13 +27,15 @@ class MoELayer:
     """
 
     def __init__(self, T, d, E, k, f, dtype, w_gate, w_up, w_down, renorm=1, prerouted=False,
-                 save_gu=True, device="cuda", w_router=None, gather=False):
+                 save_gu=True, device="cuda", w_router=None, gather=False, weight_in_forward=None):
         """w_router [E, d], if given, makes the layer start from hidden states: forward() computes the logits
         itself and backward() also returns the router's weight gradient and adds the router term to dx."""
         assert not prerouted or k == 1
         assert w_router is None or not prerouted
         self.w_router = w_router
         self.gather = gather
+        self.weight_in_forward = gather if weight_in_forward is None else bool(weight_in_forward)
+        assert gather or not self.weight_in_forward, "the weight can ride in the forward products only on the gathered path"
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
         self.P = T * k
         self.dtype, self.renorm, self.prerouted, self.save_gu = dtype, renorm, prerouted, save_gu
@@ -83,20 +87,23 @@ class MoELayer:
         if self.gather:
             L.moe_permute(None, self.topk_idx, self.offsets, self.E, out=(None, self.row_of_pair, self.pair_of_row), ws=self.ws)
             L.moe_grouped_gemm_swiglu_fwd_gather(x, self.k, self.pair_of_row, self.w_gate, self.w_up, self.w_down, self.offsets,
-                                                 save_gu=self.save_gu, out=(self.act, self.yp, self.g, self.u), ws=self.ws)
+                                                 save_gu=self.save_gu, out=(self.act, self.yp, self.g, self.u), ws=self.ws,
+                                                 topk_w=self.topk_w if self.weight_in_forward else None)
         else:
             L.moe_permute(x, self.topk_idx, self.offsets, self.E,
                           out=(self.xp, self.row_of_pair, self.pair_of_row), ws=self.ws)
             L.moe_grouped_gemm_swiglu_fwd(self.xp, self.w_gate, self.w_up, self.w_down, self.offsets,
                                           save_gu=self.save_gu, out=(self.act, self.yp, self.g, self.u), ws=self.ws)
-        L.moe_unpermute_combine_fwd(self.yp, self.topk_w, self.row_of_pair, self.T, self.k, out=self.y)
+        L.moe_unpermute_combine_fwd(self.yp, None if self.weight_in_forward else self.topk_w, self.row_of_pair, self.T, self.k,
+                                    out=self.y)
         return self.y
 
     def backward(self, dy, logits=None):
         if self.gather:
             L.moe_grouped_gemm_swiglu_bwd_gather(dy, self.x, self.topk_w, self.pair_of_row, self.g, self.u, self.w_gate,
                                                  self.w_up, self.w_down, self.offsets,
-                                                 out=(self.dxp, self.dw_gate, self.dw_up, self.dw_down, self.dw), ws=self.ws)
+                                                 out=(self.dxp, self.dw_gate, self.dw_up, self.dw_down, self.dw), ws=self.ws,
+                                                 act_w=self.act if self.weight_in_forward else None)
         else:
             L.moe_unpermute_combine_bwd(dy, self.yp, self.topk_w, self.row_of_pair, out=(self.dyp, self.dw))
             L.moe_grouped_gemm_swiglu_bwd(self.dyp, self.xp, self.g, self.u, self.act, self.w_gate, self.w_up,

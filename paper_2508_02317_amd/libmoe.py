@@ -86,11 +86,11 @@ def _load():
     lib.moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes.restype = sz
     lib.moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     lib.moe_grouped_gemm_swiglu_fwd_gather.restype = ctypes.c_int32
-    lib.moe_grouped_gemm_swiglu_fwd_gather.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_grouped_gemm_swiglu_fwd_gather.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes.restype = sz
     lib.moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
     lib.moe_grouped_gemm_swiglu_bwd_gather.restype = ctypes.c_int32
-    lib.moe_grouped_gemm_swiglu_bwd_gather.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_grouped_gemm_swiglu_bwd_gather.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.moe_unpermute_combine_fwd.restype = ctypes.c_int32
     lib.moe_unpermute_combine_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.moe_unpermute_combine_bwd.restype = ctypes.c_int32
@@ -279,8 +279,11 @@ def moe_grouped_gemm_swiglu_bwd(dyp, xp, g_save, u_save, act, w_gate, w_up, w_do
     return dxp, dwg, dwu, dwd
 
 
-def moe_grouped_gemm_swiglu_fwd_gather(x, k, pair_of_row, w_gate, w_up, w_down, offsets, save_gu=True, out=None, ws=None):
-    """Forward without xp: rows are read as x[pair_of_row[r] // k].  -> act [P,f], yp [P,d], g_save, u_save."""
+def moe_grouped_gemm_swiglu_fwd_gather(x, k, pair_of_row, w_gate, w_up, w_down, offsets, save_gu=True, out=None, ws=None, topk_w=None):
+    """Forward without xp: rows are read as x[pair_of_row[r] // k].  -> act [P,f], yp [P,d], g_save, u_save.
+    With topk_w [T,k], act and yp leave scaled by each row's combine weight."""
+    if topk_w is not None:
+        _need(topk_w, torch.float32, "topk_w")
     _need(x, None, "x"); _need(pair_of_row, torch.int32, "pair_of_row"); _need(offsets, torch.int32, "offsets")
     for name, w in (("w_gate", w_gate), ("w_up", w_up), ("w_down", w_down)):
         _need(w, x.dtype, name)
@@ -294,7 +297,7 @@ def moe_grouped_gemm_swiglu_fwd_gather(x, k, pair_of_row, w_gate, w_up, w_down, 
     act, yp, g, u = out
     code = _dtype_code(x)
     ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(code, P, d, f, E), ws, dev)
-    _check(lib.moe_grouped_gemm_swiglu_fwd_gather(_ptr(x), T, k, _ptr(pair_of_row), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+    _check(lib.moe_grouped_gemm_swiglu_fwd_gather(_ptr(x), T, k, _ptr(pair_of_row), _ptr(topk_w), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
                                                   code, P, d, f, E, _ptr(offsets), _ptr(g), _ptr(u), _ptr(act), _ptr(yp),
                                                   _ptr(ws), nbytes, _stream()))
     return act, yp, g, u
@@ -356,9 +359,12 @@ def moe_grouped_gemm_down_mx8(actq, acts, wdq, wds, offsets, out=None, ws=None):
 
 
 def moe_grouped_gemm_swiglu_bwd_gather(dy, x, topk_w, pair_of_row, g_save, u_save, w_gate, w_up, w_down, offsets,
-                                       out=None, ws=None):
+                                       out=None, ws=None, act_w=None):
     """Combine backward and FFN backward without dyp / xp.
-    -> dxp [P,d], dw_gate [E,f,d], dw_up [E,f,d], dw_down [E,d,f], dtopk_w [T,k] f32."""
+    -> dxp [P,d], dw_gate [E,f,d], dw_up [E,f,d], dw_down [E,d,f], dtopk_w [T,k] f32.
+    act_w [P,f]: the weighted activation the forward wrote when it was given topk_w (None: formed here)."""
+    if act_w is not None:
+        _need(act_w, x.dtype, "act_w")
     _need(dy, x.dtype, "dy"); _need(x, None, "x"); _need(topk_w, torch.float32, "topk_w")
     _need(pair_of_row, torch.int32, "pair_of_row"); _need(offsets, torch.int32, "offsets")
     T, d = x.shape
@@ -373,7 +379,7 @@ def moe_grouped_gemm_swiglu_bwd_gather(dy, x, topk_w, pair_of_row, g_save, u_sav
     have_saved = int(g_save is not None)
     ws, nbytes = _ws(lib.moe_grouped_gemm_swiglu_bwd_gather_workspace_bytes(code, P, d, f, E, have_saved), ws, x.device)
     _check(lib.moe_grouped_gemm_swiglu_bwd_gather(_ptr(dy), _ptr(x), T, k, _ptr(topk_w), _ptr(pair_of_row), _ptr(g_save),
-                                                  _ptr(u_save), _ptr(w_gate), _ptr(w_up), _ptr(w_down), code, P, d, f, E,
+                                                  _ptr(u_save), _ptr(act_w), _ptr(w_gate), _ptr(w_up), _ptr(w_down), code, P, d, f, E,
                                                   _ptr(offsets), _ptr(dxp), _ptr(dwg), _ptr(dwu), _ptr(dwd), _ptr(dtw),
                                                   _ptr(ws), nbytes, _stream()))
     return dxp, dwg, dwu, dwd, dtw

@@ -87,17 +87,17 @@ def test_bad_arguments_are_rejected_before_any_launch(L):
     assert lib.moe_router_bwd(one, one, one, 1, 16, 64, 16, 0, one, one, one, 8, None) == L.MOE_ERR_WORKSPACE
     assert lib.moe_router_bwd_workspace_bytes(L.MOE_BF16, 8192, 2048, 128) >= 8192 * 128 * 2
     # gathered FFN: P must be T * k, a token's row offset must fit 32 bits, null list, workspace
-    gf = lambda T, k, P, d, ws: lib.moe_grouped_gemm_swiglu_fwd_gather(one, T, k, one, one, one, one, 1, P, d, 64, 2, one, None, None, one,
+    gf = lambda T, k, P, d, ws: lib.moe_grouped_gemm_swiglu_fwd_gather(one, T, k, one, None, one, one, one, 1, P, d, 64, 2, one, None, None, one,
                                                                      one, one, ws, None)
     assert gf(8, 2, 17, 64, 1 << 30) == L.MOE_ERR_INVALID_ARG
     assert "T * k" in L.moe_last_error()
     assert gf(1 << 20, 1, 1 << 20, 4096, 1 << 40) == L.MOE_ERR_UNSUPPORTED
     assert gf(8, 2, 16, 64, 8) == L.MOE_ERR_WORKSPACE
-    assert lib.moe_grouped_gemm_swiglu_fwd_gather(one, 8, 2, None, one, one, one, 1, 16, 64, 64, 2, one, None, None, one, one, one,
+    assert lib.moe_grouped_gemm_swiglu_fwd_gather(one, 8, 2, None, None, one, one, one, 1, 16, 64, 64, 2, one, None, None, one, one, one,
                                                   1 << 30, None) == L.MOE_ERR_INVALID_ARG
-    gb = [one, one, 8, 2, one, one, one, one, one, one, one, 1, 16, 64, 64, 2, one, one, one, one, one, None, one, 1 << 30, None]
+    gb = [one, one, 8, 2, one, one, one, one, None, one, one, one, 1, 16, 64, 64, 2, one, one, one, one, one, None, one, 1 << 30, None]
     assert lib.moe_grouped_gemm_swiglu_bwd_gather(*gb) == L.MOE_ERR_INVALID_ARG       # null dtopk_w
-    gb[21] = one; gb[3] = 3
+    gb[22] = one; gb[3] = 3
     assert lib.moe_grouped_gemm_swiglu_bwd_gather(*gb) == L.MOE_ERR_INVALID_ARG       # P != T * k
     fw = lib.moe_grouped_gemm_swiglu_fwd_workspace_bytes(L.MOE_BF16, 65536, 2048, 768, 128)
     assert lib.moe_grouped_gemm_swiglu_fwd_gather_workspace_bytes(L.MOE_BF16, 65536, 2048, 768, 128) >= fw + 65536 * 4

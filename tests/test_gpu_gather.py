@@ -115,13 +115,28 @@ def test_gather_ffn_fwd_bwd(L, T, k, d, f, E, dt, kind):
     for a, b, name in zip(got2, r2 + (rdw2,), ("dxp", "dw_gate", "dw_up", "dw_down", "dtopk_w")):
         assert_close(to_np(a), b, dt, name + " (recompute)")
 
+    # the combine weight applied inside the forward products: act and yp leave scaled by the row's weight, G and U do not;
+    # the plain sum of those yp rows is Y, and the backward takes the weighted activation as it is
+    w_row = pr["w"].reshape(-1)[pr["pair_of_row"]][:, None].astype(np.float64)
+    act_w, yp_w, g_w, u_w = L.moe_grouped_gemm_swiglu_fwd_gather(tx, k, tpair, twg, twu, twd, toffs, save_gu=True, topk_w=tw)
+    assert np.array_equal(to_np(g_w), to_np(g)) and np.array_equal(to_np(u_w), to_np(u))
+    assert_close(to_np(act_w), w_row * A, dt, "w * act")
+    assert_close(to_np(yp_w), w_row * Yp, dt, "w * yp")
+    y = L.moe_unpermute_combine_fwd(yp_w, None, to_dev(pr["row_of_pair"]), T, k)
+    assert_close(to_np(y), O.unpermute_combine_fwd(Yp, pr["w"], pr["row_of_pair"], T, k), dt, "Y from weighted rows")
+    got3 = L.moe_grouped_gemm_swiglu_bwd_gather(tdy, tx, tw, tpair, to_dev(Gq, dt), to_dev(Uq, dt), twg, twu, twd, toffs,
+                                                act_w=to_dev(q(w_row * Aq, dt), dt))
+    for a, b, name in zip(got3, (rdXp, rdWg, rdWu, rdWd, rdw), ("dxp", "dw_gate", "dw_up", "dw_down", "dtopk_w")):
+        assert_close(to_np(a), b, dt, name + " (weighted activation from the forward)")
 
-def _run_layer(cfg, inp, X, gather, routing=None, save_gu=True):
+
+def _run_layer(cfg, inp, X, gather, routing=None, save_gu=True, weight_in_forward=None):
     import torch
     from paper_2508_02317_amd.layer import MoELayer
     dt = cfg.dtype
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), to_dev(inp["Wg"], dt), to_dev(inp["Wu"], dt),
-                     to_dev(inp["Wd"], dt), renorm=cfg.renorm, prerouted=routing is not None, gather=gather, save_gu=save_gu)
+                     to_dev(inp["Wd"], dt), renorm=cfg.renorm, prerouted=routing is not None, gather=gather, save_gu=save_gu,
+                     weight_in_forward=weight_in_forward)
     x, dy = to_dev(X, dt), to_dev(inp["dY"], dt)
     if routing is None:
         logits = to_dev(inp["logits"])
@@ -166,12 +181,15 @@ def test_gather_layer_end_to_end_reduced(name, save_gu):
     inp = make_inputs(cfg)
     fwd = O.moe_layer_fwd(inp["X"], inp["logits"], inp["Wg"], inp["Wu"], inp["Wd"], cfg.k, cfg.renorm)
     bwd = O.moe_layer_bwd(fwd, inp["dY"], inp["logits"], inp["Wg"], inp["Wu"], inp["Wd"], cfg.renorm)
-    layer = _run_layer(cfg, inp, inp["X"], gather=True, save_gu=save_gu)
+    layer = _run_layer(cfg, inp, inp["X"], gather=True, save_gu=save_gu)      # the default: combine weight inside the forward products
+    assert layer.weight_in_forward
     _check_layer(layer, cfg, fwd, bwd)
     assert layer.xp is None and layer.dyp is None
-    # the forward is the same arithmetic as the layer that materialises xp
+    # with the weight left to the combine, the forward is the same arithmetic as the layer that materialises xp
+    late = _run_layer(cfg, inp, inp["X"], gather=True, save_gu=save_gu, weight_in_forward=False)
+    _check_layer(late, cfg, fwd, bwd)
     plain = _run_layer(cfg, inp, inp["X"], gather=False, save_gu=save_gu)
-    assert np.array_equal(to_np(layer.y), to_np(plain.y))
+    assert np.array_equal(to_np(late.y), to_np(plain.y))
 
 
 def test_gather_layer_ep_share_reduced():
@@ -196,7 +214,7 @@ def test_gather_layer_full_size_against_the_plain_layer():
     cfg = CONFIGS["a3b_8k"]
     say("gather full size a3b_8k")
     inp = make_inputs(cfg)
-    a = _run_layer(cfg, inp, inp["X"], gather=True)
+    a = _run_layer(cfg, inp, inp["X"], gather=True, weight_in_forward=False)
     b = _run_layer(cfg, inp, inp["X"], gather=False)
     assert np.array_equal(to_np(a.row_of_pair), to_np(b.row_of_pair))
     assert np.array_equal(to_np(a.y), to_np(b.y))

@@ -86,6 +86,25 @@ def test_bad_arguments_are_rejected_before_any_launch(L):
     assert lib.moe_router_bwd(one, one, one, 1, 16, 64, 16, 0, None, one, one, 1 << 30, None) == L.MOE_ERR_INVALID_ARG
     assert lib.moe_router_bwd(one, one, one, 1, 16, 64, 16, 0, one, one, one, 8, None) == L.MOE_ERR_WORKSPACE
     assert lib.moe_router_bwd_workspace_bytes(L.MOE_BF16, 8192, 2048, 128) >= 8192 * 128 * 2
+    # 8-bit operands: reduction length a multiple of 128, null pointers, misalignment, workspace; nothing to do is fine
+    assert lib.moe_mx8_quantise(one, 4, 96, one, one, None) == L.MOE_ERR_UNSUPPORTED
+    assert "multiple of 128" in L.moe_last_error()
+    assert lib.moe_mx8_quantise(one, 4, 128, None, one, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_mx8_quantise(odd, 4, 128, one, one, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_mx8_quantise(one, -1, 128, one, one, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_mx8_quantise(None, 0, 128, None, None, None) == L.MOE_OK
+    mx = lambda T, k, pair, P, d, f, ws: lib.moe_grouped_gemm_swiglu_fwd_mx8(one, one, T, k, pair, one, one, one, one, one, one, P, d, f, 2,
+                                                                             one, one, one, one, one, ws, None)
+    assert mx(16, 1, None, 16, 128, 192, 1 << 30) == L.MOE_ERR_UNSUPPORTED           # f not a multiple of 128
+    assert mx(8, 2, one, 17, 128, 128, 1 << 30) == L.MOE_ERR_INVALID_ARG             # P != T * k
+    assert mx(1 << 22, 1, one, 1 << 22, 2048, 128, 1 << 40) == L.MOE_ERR_UNSUPPORTED   # token rows beyond 32-bit byte offsets
+    assert mx(16, 1, None, 16, 128, 128, 8) == L.MOE_ERR_WORKSPACE
+    assert mx(0, 1, None, 0, 128, 128, 0) == L.MOE_OK
+    assert lib.moe_grouped_gemm_swiglu_fwd_mx8(one, None, 16, 1, None, one, one, one, one, one, one, 16, 128, 128, 2, one, one, one, one,
+                                               one, 1 << 30, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_grouped_gemm_down_mx8(one, one, one, None, 16, 128, 128, 2, one, one, one, 1 << 30, None) == L.MOE_ERR_INVALID_ARG
+    assert lib.moe_grouped_gemm_down_mx8(one, one, one, one, 16, 128, 128, 2, one, one, one, 8, None) == L.MOE_ERR_WORKSPACE
+    assert lib.moe_grouped_gemm_swiglu_fwd_mx8_workspace_bytes(65536, 2048, 768, 128) >= 65536 * 4
     # gathered FFN: P must be T * k, a token's row offset must fit 32 bits, null list, workspace
     gf = lambda T, k, P, d, ws: lib.moe_grouped_gemm_swiglu_fwd_gather(one, T, k, one, None, one, one, one, 1, P, d, 64, 2, one, None, None, one,
                                                                      one, one, ws, None)

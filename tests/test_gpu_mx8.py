@@ -269,3 +269,55 @@ def test_forward_is_deterministic_and_replays_from_a_graph():
         for a, b in zip(outs(), eager):
             assert np.array_equal(a, b), "replay %d differs from the eager calls" % rep
         say("  replay %d identical to eager" % rep)
+
+
+def test_full_size_a3b_long_sampled():
+    """The largest configuration (40960 tokens, 327680 rows): the quantiser bit for bit on the whole input, then the forward
+    on GPU-quantised operands checked on sampled rows that the oracle computes one by one -- the first and last row of
+    twelve experts (first, last, largest, smallest and eight others), rows at row-tile boundaries and in the last,
+    partial tile of their expert."""
+    import torch
+    from paper_2508_02317_amd import libmoe as L
+    cfg = CONFIGS["a3b_long"]
+    say("mx8 full size a3b_long (sampled): T=%d P=%d" % (cfg.T, cfg.P))
+    inp = make_inputs(cfg)
+    idx, w, counts, offsets = O.route_topk(inp["logits"], cfg.k, cfg.renorm)
+    _, pair_of_row = O.permute_maps(idx, offsets)
+    E, f, d, k, P = cfg.E, cfg.f, cfg.d, cfg.k, cfg.P
+    bf = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(torch.bfloat16)
+    xq, xs = L.moe_mx8_quantise(bf(inp["X"]))
+    Xq, Xs = F.mx_quantise(inp["X"])
+    assert np.array_equal(to_np(xq), Xq) and np.array_equal(unpack_scales(to_np(xs)), Xs)
+    wq = [L.moe_mx8_quantise(bf(inp[n])) for n in ("Wg", "Wu", "Wd")]
+    actq, acts, yp = L.moe_grouped_gemm_swiglu_fwd_mx8(xq, xs, wq[0][0], wq[0][1], wq[1][0], wq[1][1], wq[2][0], wq[2][1],
+                                                       to_dev(offsets.astype(np.int32)), pair_of_row=to_dev(pair_of_row.astype(np.int32)), k=k)
+    torch.cuda.synchronize()
+    got_q, got_s, got_y = to_np(actq), unpack_scales(to_np(acts)), to_np(yp)
+    rng = np.random.default_rng(17)
+    experts = sorted(set([0, E - 1, int(np.argmax(counts)), int(np.argmin(counts))] + rng.choice(E, 8, replace=False).tolist()))
+    n_rows, flips, worst_y = 0, 0, 0.0
+    for e in experts:
+        a, b = int(offsets[e]), int(offsets[e + 1])
+        if b == a:
+            continue
+        last_tile = a + ((b - a - 1) // 256) * 256
+        rows = sorted(set([a, b - 1, min(a + 255, b - 1), min(a + 256, b - 1), last_tile, (a + b) // 2]))
+        Wg, Gs = F.mx_quantise(inp["Wg"][e]); Wu, Us = F.mx_quantise(inp["Wu"][e]); Wd, Ds = F.mx_quantise(inp["Wd"][e])
+        assert np.array_equal(to_np(wq[0][0][e]), Wg) and np.array_equal(to_np(wq[2][0][e]), Wd)       # the GPU's weight codes for this expert
+        wg, wu, wd = F.mx_dequantise(Wg, Gs), F.mx_dequantise(Wu, Us), F.mx_dequantise(Wd, Ds)
+        tok = pair_of_row[rows] // k
+        x = F.mx_dequantise(Xq[tok], Xs[tok])
+        A = F.silu(x @ wg.T) * (x @ wu.T)
+        Aq, As = F.quantise_activation(A)
+        Y = F.mx_dequantise(Aq, As) @ wd.T
+        same = got_s[rows] == As
+        assert same.mean() >= 0.99
+        step = np.maximum(_step_of_block(got_s[rows]), _step_of_block(As)).repeat(32, axis=1)
+        dA = np.abs(F.mx_dequantise(got_q[rows], got_s[rows]) - F.mx_dequantise(Aq, As)) / step
+        assert dA.max() <= 1.0 + 1e-9
+        flips += int(((got_q[rows] != Aq) | ~same.repeat(32, axis=1)).sum())
+        n_rows += len(rows)
+        worst_y = max(worst_y, float(np.max(np.abs(got_y[rows] - Y)) / np.max(np.abs(Y))))
+    say("  %d rows of %d experts: %d of %d activation codes differ, Yp max error %.2e" % (n_rows, len(experts), flips, n_rows * f, worst_y))
+    assert flips <= 5e-3 * n_rows * f
+    assert worst_y <= FUSED_YP_MAX

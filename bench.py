@@ -243,7 +243,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="a3b_8k")
+    ap.add_argument("--workload", default=None,
+                    help="one of the five configurations; default a3b_8k (the configuration the metric is quoted on), followed by a "
+                         "short run of each of the other four whose summaries go into `other_workloads` of the same line")
+    ap.add_argument("--no-others", action="store_true", help="default run only: skip the short runs of the other four configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-save-gu", action="store_true", help="backward recomputes G and U")
     ap.add_argument("--graph", action="store_true",
@@ -279,11 +282,39 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "launches": 3}))
         return
+    headline = args.workload or "a3b_8k"
+    out = measure(args, headline)
+    if args.workload is None and not args.no_others:
+        # The other configurations, briefly (no oracle leg, no 8-bit leg, fewer steps): summaries only.  The full lines
+        # come from `bench.py --workload <name>` and live in profiles/.
+        import copy
+        import gc
+        import torch as _torch
+        brief = copy.copy(args)
+        brief.no_cpu_baseline, brief.no_mx8 = True, True
+        brief.steps, brief.warmup = min(args.steps, 20), min(args.warmup, 5)
+        others = {}
+        for name in ("a3b_long", "a3b_ep_skew", "small", "tiny"):
+            gc.collect()
+            _torch.cuda.empty_cache()
+            o = measure(brief, name)
+            others[name] = {"ms_per_step_median": o["ms_per_step_median"], "value": o["value"], "unit": o["config"]["unit_note"],
+                            "steps": o["steps"], "dtype": o["dtype"], "cache_resident": o["config"]["cache_resident"],
+                            "grouped_gemm_tflops": o["grouped_gemm"]["tflops"], "grouped_gemm_frac_of_peak": o["grouped_gemm"]["frac_of_peak"],
+                            "roofline": o["roofline"], "small_launches_ms_per_step": o["small_launches_ms_per_step"]}
+        out["other_workloads"] = others
+    print(json.dumps(out), flush=True)
+
+
+def measure(args, workload):
+    """One workload: inputs, warm-up, the timed steps, per-kernel events -> the dict of the bench line."""
+    import numpy as np
+    import torch
     from paper_2508_02317_amd import libmoe as L
     from paper_2508_02317_amd.inputs import CONFIGS, make_inputs, select_local_share
     from paper_2508_02317_amd.layer import MoELayer
 
-    cfg = CONFIGS[args.workload]
+    cfg = CONFIGS[workload]
     torch.cuda.set_device(0)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     t0 = time.time()
@@ -470,7 +501,7 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp, Xh, layer, prerouted,
                                            (lidx, lw) if prerouted else None)
-    print(json.dumps(out), flush=True)
+    return out
 
 
 def cpu_baseline(cfg, inp, Xh, layer, prerouted, routing):

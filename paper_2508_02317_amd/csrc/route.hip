@@ -3,11 +3,13 @@
 // One wavefront owns one token at a time.  Lane l holds the logits of experts l, l+64, ...
 // as 64-bit keys (order-preserving float bits in the high word, the complemented expert
 // index in the low word), so a single wave-wide max implements "largest logit, ties to
-// the lower index".  k rounds of that max give the slots in order.  Each workgroup keeps
+// the lower index" (taken word by word with row shifts and row broadcasts, see wave_max_key).
+// k rounds of that max give the slots in order.  Each workgroup keeps
 // an LDS histogram of the experts it selected and writes it to its own row of the
 // workspace; a second one-block kernel sums the rows (counts) and prefix-scans them
 // (offsets).  No float atomics, no global atomics: the result is deterministic.
 #include <mutex>
+#include <type_traits>
 #include "moe_common.h"
 
 namespace moe {
@@ -16,18 +18,37 @@ constexpr int kRouteThreads = 1024;                // 16 waves: few histogram ro
 constexpr int kRouteWaves = kRouteThreads / 64;
 constexpr int kRouteMaxBlocks = 1024;
 
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o) {
-  uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), o, 64);
-  uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), o, 64);
-  return (static_cast<uint64_t>(hi) << 32) | lo;
+// Largest 32-bit value of the wave, in every lane (as a scalar).  Data-parallel primitives only: four shifts inside
+// each row of 16 lanes, then the row results are passed on to the next rows; lane 63 ends up with the maximum of all
+// 64.  Lanes shifted in from outside a row contribute 0, the identity of an unsigned maximum.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  auto dpp = [](uint32_t old, uint32_t x, auto ctrl, auto rows) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(static_cast<int>(old), static_cast<int>(x), decltype(ctrl)::value,
+                                                             decltype(rows)::value, 0xF, decltype(rows)::value == 0xF));
+  };
+  typedef std::integral_constant<int, 0xF> AllRows;
+  v = max(v, dpp(0u, v, std::integral_constant<int, 0x111>{}, AllRows{}));     // row_shr:1
+  v = max(v, dpp(0u, v, std::integral_constant<int, 0x112>{}, AllRows{}));     // row_shr:2
+  v = max(v, dpp(0u, v, std::integral_constant<int, 0x114>{}, AllRows{}));     // row_shr:4
+  v = max(v, dpp(0u, v, std::integral_constant<int, 0x118>{}, AllRows{}));     // row_shr:8: lane 15 of a row holds the row's maximum
+  v = max(v, dpp(v, v, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{}));   // row_bcast:15 into rows 1 and 3
+  v = max(v, dpp(v, v, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{}));   // row_bcast:31 into rows 2 and 3
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
 }
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+// Largest 64-bit key of the wave from the lane's VPL keys: first the largest high word, then the largest low word
+// among the keys that have it (the order of 64-bit integers, without 64-bit exchanges between lanes).
+template <int VPL>
+__device__ __forceinline__ uint64_t wave_max_key(const uint64_t (&key)[VPL]) {
+  uint32_t hi = 0u;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    uint64_t other = shfl_xor_u64(v, o);
-    v = other > v ? other : v;
-  }
-  return v;
+  for (int i = 0; i < VPL; ++i) hi = max(hi, static_cast<uint32_t>(key[i] >> 32));
+  hi = wave_max_u32(hi);
+  uint32_t lo = 0u;
+#pragma unroll
+  for (int i = 0; i < VPL; ++i)
+    if (static_cast<uint32_t>(key[i] >> 32) == hi) lo = max(lo, static_cast<uint32_t>(key[i]));
+  lo = wave_max_u32(lo);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 // float -> uint32 whose unsigned order equals the float order (-0 folded into +0 first)
 __device__ __forceinline__ uint32_t ordered_bits(float f) {
@@ -69,10 +90,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     float my_z = 0.0f;
     float zmax = 0.0f;
     for (int j = 0; j < k; ++j) {
-      uint64_t best = key[0];
-#pragma unroll
-      for (int i = 1; i < VPL; ++i) best = key[i] > best ? key[i] : best;
-      best = wave_max_u64(best);
+      const uint64_t best = wave_max_key<VPL>(key);
       int e_sel = static_cast<int>(~static_cast<uint32_t>(best));
       float z_sel = from_ordered_bits(static_cast<uint32_t>(best >> 32));
       if (j == 0) zmax = z_sel;

@@ -1377,8 +1377,7 @@ __global__ __launch_bounds__(T::kThreads) __attribute__((amdgpu_waves_per_eu(T::
 }
 
 // out[e] = bf16( sum over the chunks of a split expert, in chunk order, of its fp32 partial tiles )
-// (the split experts are taken in turn by the same blocks: with balanced routing there are none, and the launch
-// is a few hundred blocks that read one counter and leave)
+// (with balanced routing there are no split experts, and the launch is blocks that read one counter and leave)
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
   if (p.dw_partial) {                                  // dtopk_w[pair_of_row[r]] = sum over the column slots, in slot order
     for (int r = blockIdx.x * 256 + threadIdx.x; r < p.P; r += gridDim.x * 256) {
@@ -1387,24 +1386,32 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs p) {
       p.dtopk_w[min(max(p.pair_of_row[r], 0), p.P - 1)] = s;
     }
   }
+  // every (split expert, 8 outputs) pair is one unit of a single grid-strided loop: the launch is latency-bound (a unit is
+  // one round of loads and one store), so the split experts are reduced side by side, not one after the other
   const int n_split = p.items.count[1];
-  const long mn = static_cast<long>(p.M) * p.N;
-  for (int s = 0; s < n_split; ++s) {
+  const long mn = static_cast<long>(p.M) * p.N, per = mn / 8;          // N is a multiple of 8: a unit lies in one row
+  for (long unit = static_cast<long>(blockIdx.x) * 256 + threadIdx.x; unit < n_split * per; unit += static_cast<long>(gridDim.x) * 256) {
+    const int s = static_cast<int>(unit / per);
+    const long i = (unit - s * per) * 8;
     const int e = p.items.split_expert[s], n = p.items.split_n[s];
     const float* part = p.partial + static_cast<long>(p.items.split_slot0[s]) * mn;
-    for (long i = (static_cast<long>(blockIdx.x) * 256 + threadIdx.x) * 8; i < mn; i += static_cast<long>(gridDim.x) * 2048) {
-      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int j = 0; j < n; ++j) {
-        float v[8];
-        read8(part + j * mn + i, v);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < n; j += 4) {                       // four partial tiles requested together, added in slot order
+      float v[4][8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) acc[q] += v[q];
+      for (int u = 0; u < 4; ++u) read8(part + min(j + u, n - 1) * mn + i, v[u]);   // past the last slot: re-read it, not added
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (j + u < n) {
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc[q] += v[u][q];
+        }
       }
-      const int m = static_cast<int>(i / p.N), col = static_cast<int>(i % p.N);   // N is a multiple of 8: one row
-      bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
-                                  : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
-      store16(out + col, pack8(acc));
     }
+    const int m = static_cast<int>(i / p.N), col = static_cast<int>(i % p.N);
+    bf16_t* out = m < p.m_split ? p.out0 + (static_cast<long>(e) * p.m_split + m) * p.N
+                                : p.out1 + (static_cast<long>(e) * (p.M - p.m_split) + (m - p.m_split)) * p.N;
+    store16(out + col, pack8(acc));
   }
 }
 
@@ -1551,8 +1558,9 @@ static void launch_wgrad_t(WgradArgs p, hipStream_t s) {
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down" : WHICH == 1 ? "wgrad_gate_up" : "wgrad_router", (wgrad_kernel<WHICH, T, GATHER>), dim3(grid),
              dim3(T::kThreads), T::kLdsAlloc, s, p);
   // the reduction loops are grid-strided: a launch with nothing to reduce (balanced routing) should cost as little as a launch can
-  const long rblocks = std::max((static_cast<long>(p.M) * p.N + 2047) / 2048, p.dw_partial ? (static_cast<long>(p.P) + 255) / 256 : 1L);
-  const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 512L)));
+  // (room for two split experts per pass of the loop; more only repeat it)
+  const long rblocks = std::max(2 * ((static_cast<long>(p.M) * p.N + 2047) / 2048), p.dw_partial ? (static_cast<long>(p.P) + 255) / 256 : 1L);
+  const dim3 rgrid(static_cast<unsigned>(std::min(rblocks, 2048L)));
   MOE_LAUNCH(WHICH == 0 ? "wgrad_down_reduce" : WHICH == 1 ? "wgrad_gate_up_reduce" : "wgrad_router_reduce", wgrad_reduce_kernel, rgrid,
              dim3(256), 0, s, p);
 }
